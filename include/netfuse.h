@@ -1,0 +1,148 @@
+/*
+ * netfuse.h -- C ABI of the merged ("input-weight local") operators of NetFuse on MI355X (gfx950).
+ *
+ * NetFuse runs M instances of one architecture, each with its own weights and its own input,
+ * as one set of merged operators in which a weight set is paired with its own input only
+ * (Section 3).  Matrix multiplications merge into a batch matrix multiplication, convolutions
+ * into a grouped convolution whose groups are the models, layer normalisations into a group
+ * normalisation with one group per model; batch normalisation, pooling, activations and
+ * element-wise operators merge by concatenation (Section 3.1, Table 1).  The merged result is
+ * exactly the M separate results (Appendix A).
+ *
+ * Conventions for every entry point
+ *   - All pointers are DEVICE pointers on the current HIP device, owned by the caller, who
+ *     keeps them alive until `stream` has passed the call.  The library allocates nothing and
+ *     keeps no mutable global state; calls may be made from any thread.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call validates
+ *     its arguments on the host BEFORE touching HIP, enqueues its kernels and returns; it
+ *     never synchronises.  Kernels use no atomics and no hidden workspace: results are
+ *     deterministic and the calls can be captured into a HIP graph.
+ *   - Tensors are dense row-major (last index fastest) unless a stride is given.
+ *   - `dt` is the STORAGE type of activations and weight tensors (float or bfloat16 bit
+ *     patterns).  Arithmetic is always fp32 (fp32 accumulation); a bf16 output is rounded once,
+ *     to nearest even, when it is stored.  Per-feature / per-channel vectors (bias, scale,
+ *     shift, gamma, beta, mean, var) and attention masks are ALWAYS float, for either `dt`.
+ *   - Inputs are never written.  Outputs are fully overwritten.  An output may alias the
+ *     `residual` operand or (norms, pools excepted where stated) not alias anything else.
+ *   - Model order: slice m of every operand belongs to model m; nothing else is assumed.
+ *   - Errors: the return value only.  NF_EINVAL = a NULL required pointer, a non-positive or
+ *     inconsistent size, an unknown enum, or an element count that does not fit 2^31-1 where
+ *     a kernel indexes with 32 bits; NF_EUNSUPPORTED = valid arguments with no kernel;
+ *     NF_ELAUNCH = the HIP runtime refused the launch.  On any error nothing is enqueued.
+ */
+#ifndef NETFUSE_H
+#define NETFUSE_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { NF_OK = 0, NF_EINVAL = 1, NF_EUNSUPPORTED = 2, NF_ELAUNCH = 3 } nf_status;
+typedef enum { NF_F32 = 0, NF_BF16 = 1 } nf_dtype;
+typedef enum { NF_ACT_NONE = 0, NF_ACT_RELU = 1, NF_ACT_GELU = 2 /* 0.5 x (1 + erf(x / sqrt 2)) */ } nf_act;
+/* Which dimension the M models are concatenated along (the d_i of Algorithm 1). */
+typedef enum { NF_MERGE_BATCH = 0, NF_MERGE_CHANNEL = 1 } nf_merge_dim;
+
+/*
+ * Merged matrix multiplication = batch matrix multiplication (Section 3.1, "Matrix
+ * multiplication"): for every model m,   Y[m] = act(X[m] . W[m] + bias[m]) + residual[m].
+ *   X[M][N][K]   W[M][K][Nout]   bias[M][Nout] float or NULL   residual[M][N][Nout] or NULL
+ *   Y[M][N][Nout]                (N = rows of model m: batch x sequence)
+ * Y may alias residual.  The bf16 MFMA path needs K and Nout to be multiples of 8 and 16-byte
+ * aligned pointers; other shapes take a slower general kernel.
+ */
+nf_status netfuse_linear(const void* X, const void* W, const float* bias, const void* residual,
+                         void* Y, int M, int N, int K, int Nout, nf_dtype dt, nf_act act,
+                         void* stream);
+
+/*
+ * Merged convolution = grouped convolution with M*g groups (Section 3.1, "Convolution" and
+ * "Operations with input-weight local computations"; Appendix A Eq. 2-6).  Inputs and weights
+ * are concatenated along the channel dimension: x[Cin*m + ci] = x_m[ci], w[Cout*m + co] =
+ * w_m[co], y_m[co] = y[Cout*m + co].  Merged output channel c belongs to group
+ * G = c / (Cout/g) and reads merged input channels G*(Cin/g) ... G*(Cin/g) + Cin/g - 1.
+ *   x[B][M*Cin][H][W]   w[M*Cout][Cin/g][KH][KW]   y[B][M*Cout][Ho][Wo]
+ *   Ho = (H + 2 pad - dilation (KH-1) - 1)/stride + 1 (floor), Wo likewise.
+ * Zero padding, cross-correlation (no kernel flip).  Fused epilogue per output element, in this
+ * order:  v = conv + bias[c];  v = v*scale[c] + shift[c];  v += residual;  y = act(v)
+ * with bias, scale, shift float[M*Cout] or NULL (scale and shift both or neither: an inference
+ * batch normalisation folded per merged channel, see netfuse_bn_fold) and residual shaped like y
+ * or NULL.  y may alias residual.
+ */
+nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const float* scale,
+                         const float* shift, const void* residual, void* y, int M, int B, int Cin,
+                         int Cout, int g, int H, int W, int KH, int KW, int stride, int pad,
+                         int dilation, nf_dtype dt, nf_act act, void* stream);
+
+/*
+ * Merged layer normalisation = group normalisation with M groups (Section 3.1, "Layer
+ * normalization"): mean and (biased) variance of a row are taken over ONE model's H features.
+ *   layout NF_MERGE_BATCH:   x[M][rows][H]   (what the batch matmul produces)
+ *   layout NF_MERGE_CHANNEL: x[rows][M*H]    (channel concatenation, the group-norm form)
+ *   gamma, beta: float[M*H], the M affine vectors concatenated.
+ *   y = gamma (v - mean)/sqrt(var + eps) + beta,  v = x + residual (residual: like x, or NULL).
+ * y may alias x or residual.
+ */
+nf_status netfuse_layernorm(const void* x, const void* residual, const float* gamma,
+                            const float* beta, void* y, int M, int rows, int H, float eps,
+                            nf_merge_dim layout, nf_dtype dt, void* stream);
+
+/*
+ * Merged batch normalisation, inference mode (Section 3.1: per-channel, so the models'
+ * channels are concatenated).  x[B][M*C][HW]; gamma, beta, mean, var: float[M*C].
+ *   y = act(gamma (x - mean)/sqrt(var + eps) + beta + residual)     residual like x, or NULL.
+ * y may alias x or residual.
+ */
+nf_status netfuse_batchnorm(const void* x, const float* gamma, const float* beta, const float* mean,
+                            const float* var, const void* residual, void* y, int M, int B, int C,
+                            int HW, float eps, nf_dtype dt, nf_act act, void* stream);
+
+/*
+ * Per merged channel constants of an inference batch normalisation, for netfuse_conv2d's
+ * epilogue:  scale = gamma/sqrt(var + eps),  shift = beta - mean*scale.  All float[n], n = M*C.
+ */
+nf_status netfuse_bn_fold(const float* gamma, const float* beta, const float* mean, const float* var,
+                          float* scale, float* shift, int n, float eps, void* stream);
+
+/*
+ * Merged attention.  QK^T and PV are batch matrix multiplications over (sequence, head) already;
+ * merging M models multiplies the number of independent problems by M (Section 3.1, "Operations
+ * with input-weight local computations"); softmax has no weights (Section 3.1, "Non-trainable
+ * operations").  For every (m, b, head):
+ *   s_ij = scale * sum_t Q_it K_jt + mask_j;   p_ij = softmax over keys j;   O_it = sum_j p_ij V_jt
+ * Element (m, b, s, head, t) of Q, K and V lives at  ptr[m*stride_m + (b*S + s)*stride_row + head*d + t]
+ * (element units), so the three may point into one packed [M][B*S][3*heads*d] buffer.
+ * mask: float[M][B][S], additive over keys, or NULL.   O[M][B*S][heads*d] dense.
+ * Softmax is evaluated in fp32 with the row maximum subtracted.  O must not alias Q, K or V.
+ */
+nf_status netfuse_attention(const void* Q, const void* K, const void* V, const float* mask, void* O,
+                            int M, int B, int S, int heads, int d, long stride_m, long stride_row,
+                            float scale, nf_dtype dt, void* stream);
+
+/*
+ * Non-trainable operators merge by concatenation (Section 3.1, "Non-trainable operations"), so
+ * these act per channel of the channel-merged tensor; Ctot = M*C.
+ * Max pooling: x[B][Ctot][H][W] -> y[B][Ctot][Ho][Wo], window k x k, Ho = (H + 2 pad - k)/stride + 1;
+ * padded positions never win (pad < k required).
+ * Global average pooling: x[B][Ctot][HW] -> y[B][Ctot].
+ */
+nf_status netfuse_maxpool2d(const void* x, void* y, int B, int Ctot, int H, int W, int k, int stride,
+                            int pad, nf_dtype dt, void* stream);
+nf_status netfuse_avgpool_global(const void* x, void* y, int B, int Ctot, int HW, nf_dtype dt,
+                                 void* stream);
+
+/*
+ * The reshape-and-transpose that Algorithm 1 inserts where consecutive merged operators disagree
+ * on the merge dimension (Section 3.2):  to_channel != 0: src[M][rows][H] -> dst[rows][M*H];
+ * to_channel == 0: the inverse.  src and dst must not overlap.
+ */
+nf_status netfuse_merge_transpose(const void* src, void* dst, int M, int rows, int H, int to_channel,
+                                  nf_dtype dt, void* stream);
+
+/* Static description of a status code; never NULL. */
+const char* netfuse_strerror(nf_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NETFUSE_H */

@@ -1,0 +1,96 @@
+// Kernel template + launcher of the bf16 MFMA contraction; included by the gemm_inst_*.hip
+// translation units, each of which instantiates launch_gemm_bkind for one B-loader kind.
+#pragma once
+#include <atomic>
+
+#include "gemm_launch.h"
+
+namespace nf {
+
+template <class Cfg, int ALIGN_A, int BKIND>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+  unsigned id = xcd_remap(blockIdx.x, gridDim.x);
+  // consecutive ids: row tiles of one column panel, then the next panel, then the next problem,
+  // so the tiles sharing a B panel (weights of the matmul) are in flight together on one XCD.
+  const int tm = id % a.tiles_m;  id /= a.tiles_m;
+  const int tn = id % a.tiles_n;  id /= a.tiles_n;
+  const int z0 = id % a.nz0;
+  const int z1 = id / a.nz0;
+  const int row0 = tm * Cfg::kBM, col0 = tn * Cfg::kBN;
+  const int rows_left = a.rows - row0, cols_left = a.cols - col0;
+
+  ATileLoader<Cfg::kBM, ALIGN_A> la;
+  la.base = a.A + z0 * a.sA0 + z1 * a.sA1 + (long)row0 * a.lda;
+  la.lda = a.lda;
+  la.rows_left = rows_left;
+  la.K = a.K;
+  const long coff = z0 * a.sC0 + z1 * a.sC1 + (long)row0 * a.ldc + col0;
+  bf16_t* C = a.C + coff;
+  const bf16_t* R = a.R ? a.R + coff : nullptr;
+  const long rvo = z0 * a.ep.row_vec_stride0 + z1 * a.ep.row_vec_stride1 + row0;
+  const long cvo = z0 * a.ep.col_vec_stride0 + z1 * a.ep.col_vec_stride1 + col0;
+  if constexpr (BKIND == 0) {
+    BIm2colLoader<Cfg::kBN> lb;
+    lb.xg = a.B + z0 * a.sB0 + z1 * a.sB1;
+    lb.g = a.geom;
+    lb.cols_left = cols_left;
+    lb.K = a.K;
+    lb.col0 = col0;
+    gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
+  } else {
+    BDenseLoader<Cfg::kBN, BKIND> lb;
+    lb.base = a.B + z0 * a.sB0 + z1 * a.sB1 + col0;
+    lb.ldb = a.ldb;
+    lb.cols_left = cols_left;
+    lb.K = a.K;
+    gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
+  }
+}
+
+template <class Cfg, int ALIGN_A, int BKIND>
+nf_status launch_gemm(GemmLaunch& L, hipStream_t s) {
+  GemmArgs& a = L.a;
+  a.tiles_m = (a.rows + Cfg::kBM - 1) / Cfg::kBM;
+  a.tiles_n = (a.cols + Cfg::kBN - 1) / Cfg::kBN;
+  const long long total = (long long)a.tiles_m * a.tiles_n * a.nz0 * L.nz1;   // each factor < 2^31 / checked by caller
+  if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
+  auto kern = gemm_mfma_kernel<Cfg, ALIGN_A, BKIND>;
+  if (Cfg::kLdsBytes > 64 * 1024) {
+    // tiles above the default 64 KB of dynamic LDS opt in once per kernel (idempotent; a benign race)
+    static std::atomic<bool> opted_in{false};
+    if (!opted_in.load(std::memory_order_acquire)) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              Cfg::kLdsBytes) != hipSuccess)
+        return NF_ELAUNCH;
+      opted_in.store(true, std::memory_order_release);
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(256), Cfg::kLdsBytes, s, a);
+  return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
+}
+
+template <int ALIGN_A, int BKIND>
+nf_status launch_gemm_tile(int tile, GemmLaunch& L, hipStream_t s) {
+  switch (tile) {
+    case T128x128: return launch_gemm<TileCfg<128, 128, 2, 2>, ALIGN_A, BKIND>(L, s);
+    case T128x256: return launch_gemm<TileCfg<128, 256, 2, 2>, ALIGN_A, BKIND>(L, s);
+    case T256x128: return launch_gemm<TileCfg<256, 128, 2, 2>, ALIGN_A, BKIND>(L, s);
+    case T64x128: return launch_gemm<TileCfg<64, 128, 2, 2>, ALIGN_A, BKIND>(L, s);
+    case T64x64: return launch_gemm<TileCfg<64, 64, 2, 2>, ALIGN_A, BKIND>(L, s);
+    case T32x128: return launch_gemm<TileCfg<32, 128, 1, 4>, ALIGN_A, BKIND>(L, s);
+  }
+  return NF_EUNSUPPORTED;
+}
+
+// A rows that are 8- or 4-byte aligned are read with the 2-byte loader's wider siblings only
+// where a workload needs them; everything else falls to the element-wise loader.
+template <int BKIND>
+nf_status launch_gemm_bkind(int align_a, int tile, GemmLaunch& L, hipStream_t s) {
+  if (align_a >= 16) return launch_gemm_tile<16, BKIND>(tile, L, s);
+  if (align_a >= 8) return launch_gemm_tile<8, BKIND>(tile, L, s);
+  return launch_gemm_tile<2, BKIND>(tile, L, s);
+}
+
+}  // namespace nf

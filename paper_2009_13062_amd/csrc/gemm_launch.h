@@ -1,0 +1,35 @@
+// Host-side launch plumbing of the bf16 MFMA contraction kernels.  The kernel template is
+// instantiated per B-loader kind in its own translation unit (gemm_inst_*.hip) so the library
+// builds in parallel; the C ABI file only sees launch_gemm_any().
+#pragma once
+#include <hip/hip_runtime.h>
+#include <limits.h>
+
+#include "gemm_mfma.h"
+
+namespace nf {
+
+struct GemmArgs {
+  const bf16_t* A; const bf16_t* B; const bf16_t* R; bf16_t* C;
+  long lda, ldb, ldc;
+  long sA0, sA1, sB0, sB1, sC0, sC1;      // strides of the two batch coordinates (elements)
+  int rows, cols, K, nz0, tiles_m, tiles_n;
+  Epilogue ep;
+  Im2colGeom geom;                         // implicit-B convolution only
+};
+
+struct GemmLaunch {
+  GemmArgs a;
+  int nz1;
+};
+
+enum TileId { T128x128 = 0, T128x256, T256x128, T64x128, T64x64, T32x128, kNumTiles };
+constexpr int kTileBM[kNumTiles] = {128, 128, 256, 64, 64, 32};
+constexpr int kTileBN[kNumTiles] = {128, 256, 128, 128, 64, 128};
+
+// BKIND: 8 / 4 / 1 = dense B read with that vector width; 0 = implicit (im2col) B.
+// align_a: 16, 8, 4 or 2 = byte alignment of every A row start (and K a multiple of align_a/2).
+template <int BKIND>
+nf_status launch_gemm_bkind(int align_a, int tile, GemmLaunch& L, hipStream_t s);
+
+}  // namespace nf

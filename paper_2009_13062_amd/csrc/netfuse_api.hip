@@ -1,0 +1,406 @@
+// C ABI of the merged operators: argument validation on the host (before any HIP call), kernel
+// selection by (storage type, shape class), launch with the model index folded into the grid.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/netfuse.h"
+#include "attention_kernels.h"
+#include "gemm_launch.h"
+#include "gemm_mfma.h"
+#include "generic_kernels.h"
+#include "nf_common.h"
+#include "norm_kernels.h"
+
+using namespace nf;
+
+namespace {
+
+inline bool is_dtype(int dt) { return dt == NF_F32 || dt == NF_BF16; }
+inline bool is_act(int a) { return a == NF_ACT_NONE || a == NF_ACT_RELU || a == NF_ACT_GELU; }
+inline bool aligned(const void* p, size_t a) { return p == nullptr || ((uintptr_t)p % a) == 0; }
+
+// product of non-negative ints, saturating at LLONG_MAX
+inline long long prod(std::initializer_list<long long> v) {
+  long long r = 1;
+  for (long long x : v) {
+    if (x < 0) return -1;
+    if (x != 0 && r > LLONG_MAX / x) return LLONG_MAX;
+    r *= x;
+  }
+  return r;
+}
+constexpr long long kMaxElems = (1LL << 62);     // element counts must stay below this
+constexpr long long kMaxGrid = 0x7fffffffLL;
+
+inline nf_status launched() { return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH; }
+
+inline unsigned grid_for(long long total, int per_block, long long cap = 1 << 20) {
+  long long g = (total + per_block - 1) / per_block;
+  if (g > cap) g = cap;
+  if (g < 1) g = 1;
+  return (unsigned)g;
+}
+
+nf_status launch_gemm_any(int bkind, int align_a, int tile, GemmLaunch& L, hipStream_t s) {
+  switch (bkind) {
+    case 8: return launch_gemm_bkind<8>(align_a, tile, L, s);
+    case 4: return launch_gemm_bkind<4>(align_a, tile, L, s);
+    case 1: return launch_gemm_bkind<1>(align_a, tile, L, s);
+    case 0: return launch_gemm_bkind<0>(align_a, tile, L, s);
+  }
+  return NF_EUNSUPPORTED;
+}
+
+// Optional override for tile-shape sweeps: NETFUSE_TILE=<index into TileId>, read once.
+int forced_tile() {
+  static const int v = [] {
+    const char* e = getenv("NETFUSE_TILE");
+    if (!e || !*e) return -1;
+    const int t = atoi(e);
+    return (t >= 0 && t < kNumTiles) ? t : -1;
+  }();
+  return v;
+}
+
+// Tile choice: the largest tile that still yields enough workgroups to fill 256 CUs.
+int pick_tile(int rows, int cols, long long problems) {
+  const int f = forced_tile();
+  if (f >= 0) return f;
+  if (rows <= 32) return T32x128;
+  if (rows <= 64) return cols <= 64 ? T64x64 : T64x128;
+  if (cols <= 64) return T64x64;
+  auto tiles = [&](int t) {
+    return problems * ((rows + kTileBM[t] - 1) / kTileBM[t]) * ((cols + kTileBN[t] - 1) / kTileBN[t]);
+  };
+  if (rows >= 256 && tiles(T256x128) >= 1024) return T256x128;
+  if (cols >= 256 && tiles(T128x256) >= 1024) return T128x256;
+  if (tiles(T128x128) >= 256) return T128x128;
+  return T64x128;
+}
+
+// largest alignment (16, 8, 4 or 2 bytes) shared by a pointer and a row pitch / stride set
+int common_align(std::initializer_list<const void*> ptrs, std::initializer_list<long long> elem_strides) {
+  int al = 16;
+  for (const void* p : ptrs)
+    while (al > 2 && ((uintptr_t)p % al) != 0) al /= 2;
+  for (long long st : elem_strides)
+    while (al > 2 && ((st * 2) % al) != 0) al /= 2;
+  return al;
+}
+
+}  // namespace
+
+// ==========================================================================================
+extern "C" {
+
+const char* netfuse_strerror(nf_status st) {
+  switch (st) {
+    case NF_OK: return "ok";
+    case NF_EINVAL: return "invalid argument";
+    case NF_EUNSUPPORTED: return "no kernel for these arguments";
+    case NF_ELAUNCH: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+nf_status netfuse_linear(const void* X, const void* W, const float* bias, const void* residual, void* Y,
+                         int M, int N, int K, int Nout, nf_dtype dt, nf_act act, void* stream) {
+  if (!X || !W || !Y) return NF_EINVAL;
+  if (M <= 0 || N <= 0 || K <= 0 || Nout <= 0) return NF_EINVAL;
+  if (!is_dtype(dt) || !is_act(act)) return NF_EINVAL;
+  if (prod({M, N, K}) >= kMaxElems || prod({M, K, Nout}) >= kMaxElems || prod({M, N, Nout}) >= kMaxElems)
+    return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(X, esz) || !aligned(W, esz) || !aligned(Y, esz) || !aligned(residual, esz) || !aligned(bias, 4))
+    return NF_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+
+  if (dt == NF_BF16) {
+    const int al_a = common_align({X}, {K, (long long)N * K});
+    const int al_b = common_align({W}, {Nout, (long long)K * Nout});
+    // vector width of the B loader: its chunks must not straddle the end of a row
+    int bkind = 1;
+    if (al_b == 16 && Nout % 8 == 0) bkind = 8;
+    else if (al_b >= 8 && Nout % 4 == 0) bkind = 4;
+    int al = al_a;
+    while (al > 2 && (K % (al / 2)) != 0) al /= 2;
+    GemmLaunch L;
+    memset(&L, 0, sizeof(L));
+    GemmArgs& a = L.a;
+    a.A = (const bf16_t*)X; a.B = (const bf16_t*)W; a.R = (const bf16_t*)residual; a.C = (bf16_t*)Y;
+    a.lda = K; a.ldb = Nout; a.ldc = Nout;
+    a.sA0 = (long)N * K; a.sB0 = (long)K * Nout; a.sC0 = (long)N * Nout;
+    a.rows = N; a.cols = Nout; a.K = K; a.nz0 = M;
+    L.nz1 = 1;
+    a.ep.col_bias = bias; a.ep.col_vec_stride0 = Nout;
+    a.ep.act = act; a.ep.act_before_residual = 1;
+    return launch_gemm_any(bkind, al, pick_tile(N, Nout, M), L, s);
+  }
+  const int tiles_m = (N + 63) / 64, tiles_n = (Nout + 63) / 64;
+  const long long total = prod({tiles_m, tiles_n, M});
+  if (total > kMaxGrid) return NF_EUNSUPPORTED;
+  hipLaunchKernelGGL(linear_generic_kernel<float>, dim3((unsigned)total), dim3(256), 0, s, (const float*)X,
+                     (const float*)W, bias, (const float*)residual, (float*)Y, N, K, Nout, (int)act, tiles_m,
+                     tiles_n);
+  return launched();
+}
+
+nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const float* scale, const float* shift,
+                         const void* residual, void* y, int M, int B, int Cin, int Cout, int g, int H, int W,
+                         int KH, int KW, int stride, int pad, int dilation, nf_dtype dt, nf_act act,
+                         void* stream) {
+  if (!x || !w || !y) return NF_EINVAL;
+  if (M <= 0 || B <= 0 || Cin <= 0 || Cout <= 0 || g <= 0 || H <= 0 || W <= 0 || KH <= 0 || KW <= 0)
+    return NF_EINVAL;
+  if (stride <= 0 || pad < 0 || dilation <= 0) return NF_EINVAL;
+  if (Cin % g != 0 || Cout % g != 0) return NF_EINVAL;
+  if ((scale == nullptr) != (shift == nullptr)) return NF_EINVAL;
+  if (!is_dtype(dt) || !is_act(act)) return NF_EINVAL;
+  const long long eh = (long long)H + 2LL * pad - (long long)dilation * (KH - 1) - 1;
+  const long long ew = (long long)W + 2LL * pad - (long long)dilation * (KW - 1) - 1;
+  if (eh < 0 || ew < 0) return NF_EINVAL;
+  const long long Ho = eh / stride + 1, Wo = ew / stride + 1;
+  const int cig = Cin / g, cog = Cout / g;
+  const long long Ctot_in = (long long)M * Cin, Ctot_out = (long long)M * Cout;
+  if (Ctot_in > INT_MAX || Ctot_out > INT_MAX || Ho * Wo > INT_MAX || (long long)H * W > INT_MAX ||
+      prod({cig, KH, KW}) > INT_MAX || (long long)H + 2LL * pad > INT_MAX || (long long)W + 2LL * pad > INT_MAX)
+    return NF_EINVAL;
+  const long long n_in = prod({B, Ctot_in, H, W}), n_out = prod({B, Ctot_out, Ho, Wo});
+  const long long n_w = prod({Ctot_out, cig, KH, KW});
+  if (n_in >= kMaxElems || n_out >= kMaxElems || n_w >= kMaxElems) return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(x, esz) || !aligned(w, esz) || !aligned(y, esz) || !aligned(residual, esz) || !aligned(bias, 4) ||
+      !aligned(scale, 4) || !aligned(shift, 4))
+    return NF_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  const int HoWo = (int)(Ho * Wo);
+  const int Kdim = cig * KH * KW;
+
+  static const bool no_mfma_conv = getenv("NETFUSE_CONV_GENERIC") != nullptr;
+  if (dt == NF_BF16 && !no_mfma_conv) {
+    GemmLaunch L;
+    memset(&L, 0, sizeof(L));
+    GemmArgs& a = L.a;
+    a.A = (const bf16_t*)w; a.B = (const bf16_t*)x; a.R = (const bf16_t*)residual; a.C = (bf16_t*)y;
+    a.lda = Kdim; a.ldc = HoWo;
+    a.sA0 = (long)cog * Kdim; a.sA1 = 0;
+    a.sB0 = (long)cig * H * W; a.sB1 = (long)Ctot_in * H * W;
+    a.sC0 = (long)cog * HoWo; a.sC1 = (long)Ctot_out * HoWo;
+    a.rows = cog; a.cols = HoWo; a.K = Kdim; a.nz0 = M * g;
+    L.nz1 = B;
+    a.ep.row_bias = bias; a.ep.row_scale = scale; a.ep.row_shift = shift;
+    a.ep.row_vec_stride0 = cog; a.ep.row_vec_stride1 = 0;
+    a.ep.act = act; a.ep.act_before_residual = 0;
+    int al = common_align({w}, {Kdim});
+    while (al > 2 && (Kdim % (al / 2)) != 0) al /= 2;
+    const long long problems = (long long)M * g * B;
+    const int tile = pick_tile(cog, HoWo, problems);
+    const bool pointwise = KH == 1 && KW == 1 && stride == 1 && pad == 0;
+    if (pointwise) {
+      // a 1x1 convolution is a matrix product over the channel dimension with the H*W positions as
+      // columns (the converse of Section 3.1's remark that a matmul is a 1x1 convolution)
+      a.ldb = (long)H * W;
+      const int al_b = common_align({x}, {(long long)H * W});
+      int bkind = 1;
+      if (al_b == 16 && HoWo % 8 == 0) bkind = 8;
+      else if (al_b >= 8 && HoWo % 4 == 0) bkind = 4;
+      return launch_gemm_any(bkind, al, tile, L, s);
+    }
+    a.geom.H = H; a.geom.W = W; a.geom.KH = KH; a.geom.KW = KW; a.geom.Wo = (int)Wo;
+    a.geom.stride = stride; a.geom.pad = pad; a.geom.dil = dilation;
+    return launch_gemm_any(0, al, tile, L, s);
+  }
+
+  ConvGeom geo;
+  geo.B = B; geo.Ctot_in = (int)Ctot_in; geo.Ctot_out = (int)Ctot_out; geo.cig = cig; geo.cog = cog;
+  geo.H = H; geo.W = W; geo.KH = KH; geo.KW = KW; geo.Ho = (int)Ho; geo.Wo = (int)Wo;
+  geo.stride = stride; geo.pad = pad; geo.dil = dilation;
+  const unsigned grid = grid_for(n_out, 256);
+  if (dt == NF_F32)
+    hipLaunchKernelGGL(conv2d_generic_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x,
+                       (const float*)w, bias, scale, shift, (const float*)residual, (float*)y, geo, (int)act,
+                       (size_t)n_out);
+  else
+    hipLaunchKernelGGL(conv2d_generic_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)x,
+                       (const bf16_t*)w, bias, scale, shift, (const bf16_t*)residual, (bf16_t*)y, geo, (int)act,
+                       (size_t)n_out);
+  return launched();
+}
+
+nf_status netfuse_layernorm(const void* x, const void* residual, const float* gamma, const float* beta, void* y,
+                            int M, int rows, int H, float eps, nf_merge_dim layout, nf_dtype dt, void* stream) {
+  if (!x || !gamma || !beta || !y) return NF_EINVAL;
+  if (M <= 0 || rows <= 0 || H <= 0) return NF_EINVAL;
+  if (!(eps >= 0.f)) return NF_EINVAL;
+  if (layout != NF_MERGE_BATCH && layout != NF_MERGE_CHANNEL) return NF_EINVAL;
+  if (!is_dtype(dt)) return NF_EINVAL;
+  if (prod({M, rows, H}) >= kMaxElems) return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(x, esz) || !aligned(y, esz) || !aligned(residual, esz) || !aligned(gamma, 4) || !aligned(beta, 4))
+    return NF_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  const long long nrows = (long long)M * rows;
+  const long long blocks = (nrows + 3) / 4;
+  if (blocks > kMaxGrid) return NF_EUNSUPPORTED;
+  const size_t va = 4 * esz;
+  const bool vec = H % 4 == 0 && aligned(x, va) && aligned(y, va) && aligned(residual, va);
+  const int ch = layout == NF_MERGE_CHANNEL;
+#define NF_LN(T, VEC, MAXIT)                                                                             \
+  hipLaunchKernelGGL((layernorm_kernel<T, VEC, MAXIT>), dim3((unsigned)blocks), dim3(256), 0, s,         \
+                     (const T*)x, (const T*)residual, gamma, beta, (T*)y, M, rows, H, eps, ch)
+  if (dt == NF_F32) {
+    if (vec) NF_LN(float, 4, 4); else NF_LN(float, 1, 8);
+  } else {
+    if (vec) NF_LN(bf16_t, 4, 4); else NF_LN(bf16_t, 1, 8);
+  }
+#undef NF_LN
+  return launched();
+}
+
+nf_status netfuse_batchnorm(const void* x, const float* gamma, const float* beta, const float* mean,
+                            const float* var, const void* residual, void* y, int M, int B, int C, int HW,
+                            float eps, nf_dtype dt, nf_act act, void* stream) {
+  if (!x || !gamma || !beta || !mean || !var || !y) return NF_EINVAL;
+  if (M <= 0 || B <= 0 || C <= 0 || HW <= 0) return NF_EINVAL;
+  if (!(eps >= 0.f)) return NF_EINVAL;
+  if (!is_dtype(dt) || !is_act(act)) return NF_EINVAL;
+  const long long Ctot = (long long)M * C;
+  if (Ctot > INT_MAX || prod({B, Ctot, HW}) >= kMaxElems) return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(x, esz) || !aligned(y, esz) || !aligned(residual, esz) || !aligned(gamma, 4) ||
+      !aligned(beta, 4) || !aligned(mean, 4) || !aligned(var, 4))
+    return NF_EINVAL;
+  const long long rowsbc = (long long)B * Ctot;
+  if (rowsbc > kMaxGrid) return NF_EUNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  const unsigned gy = (unsigned)((HW + 1023) / 1024 > 64 ? 64 : (HW + 1023) / 1024);
+  if (dt == NF_F32)
+    hipLaunchKernelGGL(batchnorm_kernel<float>, dim3((unsigned)rowsbc, gy), dim3(256), 0, s, (const float*)x,
+                       gamma, beta, mean, var, (const float*)residual, (float*)y, (int)Ctot, HW, eps, (int)act);
+  else
+    hipLaunchKernelGGL(batchnorm_kernel<bf16_t>, dim3((unsigned)rowsbc, gy), dim3(256), 0, s, (const bf16_t*)x,
+                       gamma, beta, mean, var, (const bf16_t*)residual, (bf16_t*)y, (int)Ctot, HW, eps, (int)act);
+  return launched();
+}
+
+nf_status netfuse_bn_fold(const float* gamma, const float* beta, const float* mean, const float* var, float* scale,
+                          float* shift, int n, float eps, void* stream) {
+  if (!gamma || !beta || !mean || !var || !scale || !shift) return NF_EINVAL;
+  if (n <= 0 || !(eps >= 0.f)) return NF_EINVAL;
+  if (!aligned(gamma, 4) || !aligned(beta, 4) || !aligned(mean, 4) || !aligned(var, 4) || !aligned(scale, 4) ||
+      !aligned(shift, 4))
+    return NF_EINVAL;
+  hipLaunchKernelGGL(bn_fold_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, gamma,
+                     beta, mean, var, scale, shift, n, eps);
+  return launched();
+}
+
+nf_status netfuse_attention(const void* Q, const void* K, const void* V, const float* mask, void* O, int M, int B,
+                            int S, int heads, int d, long stride_m, long stride_row, float scale, nf_dtype dt,
+                            void* stream) {
+  if (!Q || !K || !V || !O) return NF_EINVAL;
+  if (M <= 0 || B <= 0 || S <= 0 || heads <= 0 || d <= 0) return NF_EINVAL;
+  if (!is_dtype(dt) || !(scale == scale)) return NF_EINVAL;
+  const long long hd = (long long)heads * d;
+  if (hd > INT_MAX) return NF_EINVAL;
+  if (stride_row < hd) return NF_EINVAL;                              // heads of one row are side by side
+  if (prod({B, S}) > INT_MAX / 2) return NF_EINVAL;
+  if (stride_m < 0 || (M > 1 && stride_m < (long long)(B * (long long)S - 1) * stride_row + hd)) return NF_EINVAL;
+  if (prod({M, B, S, hd}) >= kMaxElems || prod({M, stride_m}) >= kMaxElems) return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(Q, esz) || !aligned(K, esz) || !aligned(V, esz) || !aligned(O, esz) || !aligned(mask, 4))
+    return NF_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  AttnArgs a;
+  a.Q = Q; a.K = K; a.V = V; a.mask = mask; a.O = O;
+  a.M = M; a.B = B; a.S = S; a.heads = heads; a.d = d;
+  a.stride_m = stride_m; a.stride_row = stride_row; a.scale = scale;
+
+  if (dt == NF_BF16 && d == kAttnD && stride_row % 8 == 0 && stride_m % 8 == 0 && aligned(Q, 16) &&
+      aligned(K, 16) && aligned(V, 16) && aligned(O, 8)) {
+    const int qblocks = (S + 127) / 128;
+    const long long total = prod({M, B, heads, qblocks});
+    if (total > kMaxGrid) return NF_EUNSUPPORTED;
+    hipLaunchKernelGGL(attention_mfma_d64_kernel, dim3((unsigned)total), dim3(256), 0, s, a, qblocks);
+    return launched();
+  }
+  if (d > 256) return NF_EUNSUPPORTED;
+  const long long waves = prod({M, B, heads, S});
+  const long long blocks = (waves + 3) / 4;
+  if (blocks > kMaxGrid) return NF_EUNSUPPORTED;
+  const int dpl = (d + 63) / 64;
+#define NF_ATT(T, DPL) \
+  hipLaunchKernelGGL((attention_generic_kernel<T, DPL>), dim3((unsigned)blocks), dim3(256), 0, s, a)
+  if (dt == NF_F32) {
+    if (dpl == 1) NF_ATT(float, 1); else if (dpl == 2) NF_ATT(float, 2); else NF_ATT(float, 4);
+  } else {
+    if (dpl == 1) NF_ATT(bf16_t, 1); else if (dpl == 2) NF_ATT(bf16_t, 2); else NF_ATT(bf16_t, 4);
+  }
+#undef NF_ATT
+  return launched();
+}
+
+nf_status netfuse_maxpool2d(const void* x, void* y, int B, int Ctot, int H, int W, int k, int stride, int pad,
+                            nf_dtype dt, void* stream) {
+  if (!x || !y) return NF_EINVAL;
+  if (B <= 0 || Ctot <= 0 || H <= 0 || W <= 0 || k <= 0 || stride <= 0 || pad < 0) return NF_EINVAL;
+  if (pad >= k || !is_dtype(dt)) return NF_EINVAL;
+  if ((long long)H + 2LL * pad < k || (long long)W + 2LL * pad < k) return NF_EINVAL;
+  const int Ho = (H + 2 * pad - k) / stride + 1, Wo = (W + 2 * pad - k) / stride + 1;
+  const long long n_in = prod({B, Ctot, H, W}), n_out = prod({B, Ctot, Ho, Wo});
+  if (n_in >= kMaxElems || n_out >= kMaxElems) return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(x, esz) || !aligned(y, esz)) return NF_EINVAL;
+  const unsigned grid = grid_for(n_out, 256);
+  hipStream_t s = (hipStream_t)stream;
+  if (dt == NF_F32)
+    hipLaunchKernelGGL(maxpool2d_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x, (float*)y, H, W, Ho,
+                       Wo, k, stride, pad, (size_t)n_out);
+  else
+    hipLaunchKernelGGL(maxpool2d_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, H, W,
+                       Ho, Wo, k, stride, pad, (size_t)n_out);
+  return launched();
+}
+
+nf_status netfuse_avgpool_global(const void* x, void* y, int B, int Ctot, int HW, nf_dtype dt, void* stream) {
+  if (!x || !y) return NF_EINVAL;
+  if (B <= 0 || Ctot <= 0 || HW <= 0 || !is_dtype(dt)) return NF_EINVAL;
+  if (prod({B, Ctot, HW}) >= kMaxElems) return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(x, esz) || !aligned(y, esz)) return NF_EINVAL;
+  const long long nchan = (long long)B * Ctot;
+  const long long blocks = (nchan + 3) / 4;
+  if (blocks > kMaxGrid) return NF_EUNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  if (dt == NF_F32)
+    hipLaunchKernelGGL(avgpool_global_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)x,
+                       (float*)y, (size_t)nchan, HW);
+  else
+    hipLaunchKernelGGL(avgpool_global_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)x,
+                       (bf16_t*)y, (size_t)nchan, HW);
+  return launched();
+}
+
+nf_status netfuse_merge_transpose(const void* src, void* dst, int M, int rows, int H, int to_channel, nf_dtype dt,
+                                  void* stream) {
+  if (!src || !dst || src == dst) return NF_EINVAL;
+  if (M <= 0 || rows <= 0 || H <= 0 || !is_dtype(dt)) return NF_EINVAL;
+  const long long total = prod({M, rows, H});
+  if (total >= kMaxElems) return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(src, esz) || !aligned(dst, esz)) return NF_EINVAL;
+  const unsigned grid = grid_for(total, 256);
+  hipStream_t s = (hipStream_t)stream;
+  if (dt == NF_F32)
+    hipLaunchKernelGGL(merge_transpose_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)src, (float*)dst,
+                       M, rows, H, to_channel != 0, (size_t)total);
+  else
+    hipLaunchKernelGGL(merge_transpose_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)src,
+                       (bf16_t*)dst, M, rows, H, to_channel != 0, (size_t)total);
+  return launched();
+}
+
+}  // extern "C"

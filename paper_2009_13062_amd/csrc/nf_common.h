@@ -1,0 +1,64 @@
+// Shared device-side helpers of the merged-operator kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/netfuse.h"
+
+namespace nf {
+
+typedef uint16_t bf16_t;   // bfloat16 bit pattern as stored in HBM
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+
+constexpr int kWave = 64;          // CDNA wavefront width
+constexpr int kNumXcd = 8;         // MI355X: 8 XCDs, workgroups are dealt to them round-robin
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// Round to nearest even; NaN stays a (quiet) NaN.
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float load_f32(const T* p);
+template <> __device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+
+template <typename T> __device__ __forceinline__ void store_f32(T* p, float v);
+template <> __device__ __forceinline__ void store_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_f32<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == NF_ACT_RELU) return v > 0.f ? v : (v != v ? v : 0.f);
+  if (act == NF_ACT_GELU) return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
+  return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+  return v;
+}
+
+// Workgroups are handed to the 8 XCDs round-robin (id % 8), and each XCD has its own L2.  This
+// maps the hardware id to a logical id such that consecutive logical ids run on the same XCD, so
+// tiles that share operands (the tiles of one model) share an L2.  Bijective for any total.
+__device__ __forceinline__ unsigned xcd_remap(unsigned hw_id, unsigned total) {
+  const unsigned xcd = hw_id % kNumXcd, local = hw_id / kNumXcd;
+  const unsigned base = total / kNumXcd, rem = total % kNumXcd;
+  const unsigned start = xcd * base + (xcd < rem ? xcd : rem);
+  return start + local;
+}
+
+}  // namespace nf

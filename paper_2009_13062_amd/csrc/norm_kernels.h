@@ -1,0 +1,233 @@
+// HBM-bound kernels: merged layer norm (one wavefront per row of one model), merged inference
+// batch norm, its folding into scale/shift, pools and the merge-dimension transpose.
+#pragma once
+#include "nf_common.h"
+
+namespace nf {
+
+template <typename T, int VEC> struct VecIO;
+template <> struct VecIO<float, 4> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+template <> struct VecIO<bf16_t, 4> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[4]) {
+    const uint2 t = *reinterpret_cast<const uint2*>(p);
+    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[4]) {
+    uint2 t;
+    t.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+    t.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+    *reinterpret_cast<uint2*>(p) = t;
+  }
+};
+template <typename T> struct VecIO<T, 1> {
+  static __device__ __forceinline__ void load(const T* p, float (&v)[1]) { v[0] = load_f32(p); }
+  static __device__ __forceinline__ void store(T* p, const float (&v)[1]) { store_f32(p, v[0]); }
+};
+
+// Merged layer norm = group norm with M groups (Section 3.1).  One 64-lane wavefront owns one
+// (model, row): statistics are reduced across the lanes, never across models.  A row of up to
+// 64*VEC*MAXIT features stays in registers between the passes (x and residual are read once);
+// longer rows are re-read from L2.  mean, then mean of squared deviations (biased), in fp32.
+template <typename T, int VEC, int MAXIT>
+__global__ __launch_bounds__(256) void layernorm_kernel(
+    const T* x, const T* residual, const float* __restrict__ gamma, const float* __restrict__ beta,
+    T* y, int M, int rows, int H, float eps, int channel_layout) {
+  const int lane = threadIdx.x % kWave;
+  const long wrow = (long)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;   // m*rows + r
+  if (wrow >= (long)M * rows) return;
+  const int m = (int)(wrow / rows), r = (int)(wrow % rows);
+  const size_t base = channel_layout ? ((size_t)r * M + m) * H : ((size_t)m * rows + r) * H;
+  const T* xr = x + base;
+  const T* rr = residual ? residual + base : nullptr;
+  const float* gm = gamma + (size_t)m * H;
+  const float* bt = beta + (size_t)m * H;
+  const bool cached = H <= kWave * VEC * MAXIT;
+  float v[MAXIT][VEC];
+  float sum = 0.f;
+  if (cached) {
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it) {
+      const int i = (it * kWave + lane) * VEC;
+      if (i < H) {
+        VecIO<T, VEC>::load(xr + i, v[it]);
+        if (rr) {
+          float t[VEC];
+          VecIO<T, VEC>::load(rr + i, t);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) v[it][e] += t[e];
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sum += v[it][e];
+      }
+    }
+  } else {
+    for (int i = lane * VEC; i < H; i += kWave * VEC) {
+      float a[VEC];
+      VecIO<T, VEC>::load(xr + i, a);
+      if (rr) {
+        float t[VEC];
+        VecIO<T, VEC>::load(rr + i, t);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a[e] += t[e];
+      }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sum += a[e];
+    }
+  }
+  const float mean = wave_sum(sum) / (float)H;
+  float sq = 0.f;
+  if (cached) {
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it) {
+      const int i = (it * kWave + lane) * VEC;
+      if (i < H) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { const float dlt = v[it][e] - mean; sq = fmaf(dlt, dlt, sq); }
+      }
+    }
+  } else {
+    for (int i = lane * VEC; i < H; i += kWave * VEC) {
+      float a[VEC];
+      VecIO<T, VEC>::load(xr + i, a);
+      if (rr) {
+        float t[VEC];
+        VecIO<T, VEC>::load(rr + i, t);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a[e] += t[e];
+      }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { const float dlt = a[e] - mean; sq = fmaf(dlt, dlt, sq); }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)H + eps);
+  T* yr = y + base;
+  if (cached) {
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it) {
+      const int i = (it * kWave + lane) * VEC;
+      if (i < H) {
+        float o[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) o[e] = fmaf((v[it][e] - mean) * rstd, gm[i + e], bt[i + e]);
+        VecIO<T, VEC>::store(yr + i, o);
+      }
+    }
+  } else {
+    for (int i = lane * VEC; i < H; i += kWave * VEC) {
+      float a[VEC], o[VEC];
+      VecIO<T, VEC>::load(xr + i, a);
+      if (rr) {
+        float t[VEC];
+        VecIO<T, VEC>::load(rr + i, t);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a[e] += t[e];
+      }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) o[e] = fmaf((a[e] - mean) * rstd, gm[i + e], bt[i + e]);
+      VecIO<T, VEC>::store(yr + i, o);
+    }
+  }
+}
+
+// Merged inference batch norm (Section 3.1): per merged channel c of x[B][Ctot][HW].
+// One workgroup row per (b, c); gridDim.y splits long HW.
+template <typename T>
+__global__ __launch_bounds__(256) void batchnorm_kernel(
+    const T* x, const float* __restrict__ gamma, const float* __restrict__ beta,
+    const float* __restrict__ mean, const float* __restrict__ var, const T* residual, T* y,
+    int Ctot, int HW, float eps, int act) {
+  const size_t bc = blockIdx.x;
+  const int c = (int)(bc % Ctot);
+  const float s = gamma[c] / sqrtf(var[c] + eps);
+  const float mu = mean[c], bta = beta[c];
+  const size_t base = bc * (size_t)HW;
+  for (int p = blockIdx.y * 256 + threadIdx.x; p < HW; p += gridDim.y * 256) {
+    float v = fmaf(load_f32(x + base + p) - mu, s, bta);
+    if (residual) v += load_f32(residual + base + p);
+    store_f32(y + base + p, apply_act(v, act));
+  }
+}
+
+__global__ __launch_bounds__(256) void bn_fold_kernel(
+    const float* __restrict__ gamma, const float* __restrict__ beta, const float* __restrict__ mean,
+    const float* __restrict__ var, float* scale, float* shift, int n, float eps) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= n) return;
+  const float s = gamma[c] / sqrtf(var[c] + eps);
+  scale[c] = s;
+  shift[c] = beta[c] - mean[c] * s;
+}
+
+// Max pooling per channel of the channel-merged tensor (Section 3.1, non-trainable operators).
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool2d_kernel(const T* __restrict__ x, T* y, int H, int W,
+                                                        int Ho, int Wo, int k, int stride, int pad,
+                                                        size_t total) {
+  for (size_t o = (size_t)blockIdx.x * 256 + threadIdx.x; o < total; o += (size_t)gridDim.x * 256) {
+    const int ox = (int)(o % Wo);
+    size_t t = o / Wo;
+    const int oy = (int)(t % Ho);
+    const size_t bc = t / Ho;
+    const T* xc = x + bc * (size_t)H * W;
+    float best = -INFINITY;
+    for (int ky = 0; ky < k; ++ky) {
+      const int iy = oy * stride + ky - pad;
+      if (iy < 0 || iy >= H) continue;
+      for (int kx = 0; kx < k; ++kx) {
+        const int ix = ox * stride + kx - pad;
+        if (ix < 0 || ix >= W) continue;
+        const float v = load_f32(xc + (size_t)iy * W + ix);
+        best = v > best ? v : best;
+      }
+    }
+    store_f32(y + o, best);
+  }
+}
+
+// Global average pooling: one wavefront per (b, channel).
+template <typename T>
+__global__ __launch_bounds__(256) void avgpool_global_kernel(const T* __restrict__ x, T* y, size_t nchan,
+                                                             int HW) {
+  const int lane = threadIdx.x % kWave;
+  const size_t ch = (size_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (ch >= nchan) return;
+  const T* xc = x + ch * (size_t)HW;
+  float s = 0.f;
+  for (int p = lane; p < HW; p += kWave) s += load_f32(xc + p);
+  s = wave_sum(s);
+  if (lane == 0) store_f32(y + ch, s / (float)HW);
+}
+
+// Batch-merged [M][rows][H] <-> channel-merged [rows][M*H] (Section 3.2, Algorithm 1's reshape).
+// Index o runs over the destination, so writes are fully coalesced; reads are H-contiguous runs.
+template <typename T>
+__global__ __launch_bounds__(256) void merge_transpose_kernel(const T* __restrict__ src, T* dst, int M,
+                                                              int rows, int H, int to_channel,
+                                                              size_t total) {
+  for (size_t o = (size_t)blockIdx.x * 256 + threadIdx.x; o < total; o += (size_t)gridDim.x * 256) {
+    const int i = (int)(o % H);
+    size_t t = o / H;
+    size_t s;
+    if (to_channel) {            // dst[r][m][i] <- src[m][r][i]
+      const int m = (int)(t % M);
+      const size_t r = t / M;
+      s = ((size_t)m * rows + r) * H + i;
+    } else {                     // dst[m][r][i] <- src[r][m][i]
+      const int r = (int)(t % rows);
+      const size_t m = t / rows;
+      s = ((size_t)r * M + m) * H + i;
+    }
+    dst[o] = src[s];
+  }
+}
+
+}  // namespace nf

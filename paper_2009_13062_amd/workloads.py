@@ -1,0 +1,173 @@
+"""The op sequences of the five workloads, expressed as calls into the merged-operator library.
+
+Each class owns its weights (torch CUDA tensors in the merged layouts of include/netfuse.h) and
+pre-allocates every activation buffer, so ``forward`` only enqueues kernels on the current
+stream: it allocates nothing and can be captured into a HIP graph.  ``per_model()`` returns M
+instances of the same class bound to model m's slices with M = 1 -- the same kernels launched
+once per model, i.e. the "one model after the other" way of serving that merging replaces
+(Section 5.1's Sequential baseline).
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import torch
+
+import paper_2009_13062_amd as nf
+
+
+def to_device(a, dtype: torch.dtype, device="cuda") -> torch.Tensor:
+    """numpy float32 array -> contiguous device tensor of the storage dtype."""
+    t = torch.from_numpy(a) if not isinstance(a, torch.Tensor) else a
+    return t.to(device=device, dtype=dtype).contiguous()
+
+
+class EncoderStack:
+    """Post-LN encoder layers on X[M, batch*seq, hidden] (workloads 2 and 5):
+    QKV = X Wqkv + b; A = attention(QKV); X1 = LN(A Wo + bo + X); X2 = LN(GELU(X1 W1 + b1) W2 + b2 + X1)."""
+
+    MATS = ("Wqkv", "Wo", "W1", "W2")
+
+    def __init__(self, layers: List[Dict[str, torch.Tensor]], M: int, batch: int, seq: int, heads: int,
+                 eps: float = 1e-5, buffers: Optional[Dict[str, torch.Tensor]] = None):
+        self.layers, self.M, self.batch, self.seq, self.heads, self.eps = layers, M, batch, seq, heads, eps
+        W = layers[0]
+        self.hidden, self.ffn = W["Wqkv"].shape[1], W["W1"].shape[2]
+        N, Hd, F = batch * seq, self.hidden, self.ffn
+        dt, dev = W["Wqkv"].dtype, W["Wqkv"].device
+        if buffers is None:
+            e = lambda *s: torch.empty(s, dtype=dt, device=dev)
+            buffers = dict(qkv=e(M, N, 3 * Hd), att=e(M, N, Hd), h=e(M, N, Hd), x1=e(M, N, Hd),
+                           f1=e(M, N, F), f2=e(M, N, Hd), xa=e(M, N, Hd), xb=e(M, N, Hd))
+        self.buf = buffers
+
+    @classmethod
+    def from_numpy(cls, inp, M, batch, seq, heads, dtype=torch.bfloat16, eps=1e-5):
+        layers = []
+        for Lw in inp["layers"]:
+            layers.append({k: to_device(v, dtype if k in cls.MATS else torch.float32) for k, v in Lw.items()})
+        return cls(layers, M, batch, seq, heads, eps)
+
+    def layer(self, X, Lw, out, trace=None):
+        b, M = self.buf, self.M
+        nf.linear(X, Lw["Wqkv"], bias=Lw["bqkv"], out=b["qkv"])
+        nf.attention_packed(b["qkv"], self.batch, self.seq, self.heads, out=b["att"])
+        nf.linear(b["att"], Lw["Wo"], bias=Lw["bo"], residual=X, out=b["h"])
+        nf.layernorm(b["h"], Lw["ln1_g"], Lw["ln1_b"], M, eps=self.eps, out=b["x1"])
+        nf.linear(b["x1"], Lw["W1"], bias=Lw["b1"], act=nf.ACT_GELU, out=b["f1"])
+        nf.linear(b["f1"], Lw["W2"], bias=Lw["b2"], residual=b["x1"], out=b["f2"])
+        nf.layernorm(b["f2"], Lw["ln2_g"], Lw["ln2_b"], M, eps=self.eps, out=out)
+        if trace is not None:
+            trace.append({k: b[k].clone() for k in ("qkv", "att", "h", "x1", "f1", "f2")} | {"x2": out.clone()})
+        return out
+
+    def forward(self, X, trace=None):
+        outs = (self.buf["xa"], self.buf["xb"])
+        for i, Lw in enumerate(self.layers):
+            X = self.layer(X, Lw, outs[i % 2], trace)
+        return X
+
+    def per_model(self):
+        Hd = self.hidden
+        out = []
+        for m in range(self.M):
+            layers = []
+            for Lw in self.layers:
+                d = {}
+                for k, v in Lw.items():
+                    d[k] = v[m * Hd:(m + 1) * Hd] if k.startswith("ln") else v[m:m + 1]
+                layers.append(d)
+            bufs = {k: v[m:m + 1] for k, v in self.buf.items()}
+            out.append(EncoderStack(layers, 1, self.batch, self.seq, self.heads, self.eps, bufs))
+        return out
+
+
+class ResNetForward:
+    """Bottleneck ResNet / ResNeXt forward on x[1, M*3, image, image] -> [1, M*C_last] (workloads 3, 4).
+    Inference batch norm enters every convolution as its per-channel scale/shift epilogue."""
+
+    def __init__(self, spec, params: Dict[str, Dict[str, torch.Tensor]], M: int, dtype=torch.bfloat16,
+                 eps: float = 1e-5, device="cuda", _shared=None):
+        self.spec, self.M, self.eps = spec, M, eps
+        self.P = params
+        if _shared is not None:
+            self.fold, self.buf = _shared
+            return
+        self.fold = {}
+        for c in spec.convs():
+            p = params[c.name]
+            self.fold[c.name] = nf.bn_fold(p["gamma"], p["beta"], p["mean"], p["var"], eps=eps)
+        # activation buffers, one per op output
+        self.buf = {}
+        e = lambda ch, hw: torch.empty((1, M * ch, hw, hw), dtype=dtype, device=device)
+        hw = nf.conv_out_size(spec.image, 7, 2, 3)
+        self.buf["stem"] = e(spec.stem.cout, hw)
+        hw = (hw + 2 - 3) // 2 + 1
+        self.buf["maxpool"] = e(spec.stem.cout, hw)
+        for blk in spec.blocks:
+            self.buf[blk.conv1.name] = e(blk.conv1.cout, hw)
+            hw2 = nf.conv_out_size(hw, 3, blk.conv2.stride, 1)
+            self.buf[blk.conv2.name] = e(blk.conv2.cout, hw2)
+            if blk.down is not None:
+                self.buf[blk.down.name] = e(blk.down.cout, hw2)
+            self.buf[blk.conv3.name] = e(blk.conv3.cout, hw2)
+            hw = hw2
+        self.buf["avgpool"] = torch.empty((1, M * spec.out_channels), dtype=dtype, device=device)
+
+    @classmethod
+    def from_numpy(cls, inp, spec, M, dtype=torch.bfloat16, eps=1e-5):
+        params = {}
+        for name, p in inp["params"].items():
+            params[name] = {k: to_device(v, dtype if k == "w" else torch.float32) for k, v in p.items()}
+        return cls(spec, params, M, dtype, eps)
+
+    def _conv(self, x, c, act, residual=None):
+        scale, shift = self.fold[c.name]
+        return nf.conv2d(x, self.P[c.name]["w"], self.M, g=c.groups, scale=scale, shift=shift,
+                         residual=residual, stride=c.stride, pad=c.pad, act=act, out=self.buf[c.name])
+
+    def forward(self, x):
+        s = self.spec
+        x = self._conv(x, s.stem, nf.ACT_RELU)
+        x = nf.maxpool2d(x, 3, 2, 1, out=self.buf["maxpool"])
+        for blk in s.blocks:
+            a = self._conv(x, blk.conv1, nf.ACT_RELU)
+            b = self._conv(a, blk.conv2, nf.ACT_RELU)
+            sc = self._conv(x, blk.down, nf.ACT_NONE) if blk.down is not None else x
+            x = self._conv(b, blk.conv3, nf.ACT_RELU, residual=sc)
+        return nf.avgpool_global(x, out=self.buf["avgpool"])
+
+    def per_model(self):
+        out = []
+        M = self.M
+        for m in range(M):
+            P, fold, buf = {}, {}, {}
+            for c in self.spec.convs():
+                sl = slice(m * c.cout, (m + 1) * c.cout)
+                P[c.name] = {"w": self.P[c.name]["w"][sl]}
+                fold[c.name] = (self.fold[c.name][0][sl], self.fold[c.name][1][sl])
+            for k, v in self.buf.items():
+                ch = v.shape[1] // M
+                buf[k] = v[:, m * ch:(m + 1) * ch]
+            out.append(ResNetForward(self.spec, P, 1, eps=self.eps, _shared=(fold, buf)))
+        return out
+
+    def slice_input(self, x, m):
+        return x[:, 3 * m:3 * (m + 1)]
+
+
+class TinyLayer:
+    """Workload 1: batch-merged linear -> per-model LayerNorm (Section 3.2's two-layer example),
+    and the merged 3x3 convolution on its own input."""
+
+    def __init__(self, inp, M, dtype=torch.float32):
+        self.M = M
+        self.t = {k: to_device(v, dtype if k in ("X", "W", "conv_x", "conv_w") else torch.float32)
+                  for k, v in inp.items()}
+
+    def forward(self):
+        t, M = self.t, self.M
+        Y = nf.linear(t["X"], t["W"], bias=t["b"])
+        Z = nf.layernorm(Y, t["gamma"], t["beta"], M, eps=1e-5)
+        C = nf.conv2d(t["conv_x"], t["conv_w"], M, g=1, stride=1, pad=1)
+        return {"linear": Y, "layernorm": Z, "conv": C}
