@@ -66,31 +66,31 @@ class OpTimer:
         setattr(self.nf, name, wrapped)
 
     def __enter__(self):
-        def d_linear(out, X, W, bias=None, residual=None, act=0, **kw):
+        def d_linear(y_, X, W, bias=None, residual=None, act=0, **kw):
             M, N, K = X.shape
             No = W.shape[2]
             e = X.element_size()
-            by = e * (X.numel() + W.numel() + out.numel() * (2 if residual is not None else 1)) + (4 * M * No if bias is not None else 0)
+            by = e * (X.numel() + W.numel() + y_.numel() * (2 if residual is not None else 1)) + (4 * M * No if bias is not None else 0)
             return "linear_%dx%dx%d" % (N, K, No), 2.0 * M * N * K * No, by
 
-        def d_conv(out, x, w, M, g=1, bias=None, scale=None, shift=None, residual=None, stride=1, pad=0, **kw):
+        def d_conv(y_, x, w, M, g=1, bias=None, scale=None, shift=None, residual=None, stride=1, pad=0, **kw):
             e = x.element_size()
-            fl = 2.0 * out.numel() * w.shape[1] * w.shape[2] * w.shape[3]
-            by = e * (x.numel() + w.numel() + out.numel() * (2 if residual is not None else 1)) + (8 * w.shape[0] if scale is not None else 0)
+            fl = 2.0 * y_.numel() * w.shape[1] * w.shape[2] * w.shape[3]
+            by = e * (x.numel() + w.numel() + y_.numel() * (2 if residual is not None else 1)) + (8 * w.shape[0] if scale is not None else 0)
             tag = "conv%dx%d_s%d_g%d_%d->%d@%d" % (w.shape[2], w.shape[3], stride, g, x.shape[1] // M, w.shape[0] // M, x.shape[2])
             return tag, fl, by
 
-        def d_attn(out, QKV, B, S, heads, **kw):
+        def d_attn(y_, QKV, B, S, heads, **kw):
             M, N, th = QKV.shape
-            return "attention_S%d" % S, 4.0 * M * B * heads * S * S * (th // 3 // heads), QKV.element_size() * (QKV.numel() + out.numel())
+            return "attention_S%d" % S, 4.0 * M * B * heads * S * S * (th // 3 // heads), QKV.element_size() * (QKV.numel() + y_.numel())
 
-        def d_ln(out, x, gamma, beta, M, residual=None, **kw):
+        def d_ln(y_, x, gamma, beta, M, residual=None, **kw):
             by = x.element_size() * x.numel() * (3 if residual is not None else 2) + 8 * gamma.numel()
             return "layernorm_H%d" % (gamma.numel() // M), 8.0 * x.numel(), by
 
         def d_pool(tag):
-            def d(out, x, *a, **kw):
-                return tag, float(x.numel()), x.element_size() * (x.numel() + out.numel())
+            def d(y_, x, *a, **kw):
+                return tag, float(x.numel()), x.element_size() * (x.numel() + y_.numel())
             return d
 
         self._wrap("linear", d_linear)
