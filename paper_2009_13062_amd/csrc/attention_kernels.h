@@ -90,6 +90,20 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a) {
 // for its B operand (O^T = V^T P^T), with the key order inside a 16-key step permuted identically
 // on the V^T side.  V is transposed 8x8 in registers on its way into LDS.
 // ------------------------------------------------------------------------------------------
+// 8 (key) x 8 (feature) block held as 8 rows of 4 dwords -> 8 vectors of 8 consecutive keys.
+__device__ __forceinline__ void transpose_8x8_b16(const uint32_t (&in)[8][4], uint4 (&out)[8]) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    uint32_t w[4];
+#pragma unroll
+    for (int kp = 0; kp < 4; ++kp) {
+      const uint32_t lo = in[2 * kp][e / 2], hi = in[2 * kp + 1][e / 2];
+      w[kp] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+    }
+    out[e] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
 constexpr int kAttnD = 64;
 constexpr int kAttnKB = 64;                 // keys per LDS stage
 constexpr int kAttnKPitch = kAttnD + 8;     // K tile  [key][t]
@@ -150,7 +164,7 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
         in[r][0] = v.x; in[r][1] = v.y; in[r][2] = v.z; in[r][3] = v.w;
       }
       uint4 out[8];
-      transpose_k8<8>(in, out);
+      transpose_8x8_b16(in, out);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         uint2* dst = reinterpret_cast<uint2*>(Vt + (tc + e) * kAttnVPitch + kb);

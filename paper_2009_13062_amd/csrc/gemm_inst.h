@@ -10,7 +10,7 @@ namespace nf {
 template <class Cfg, int ALIGN_A, int BKIND>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+  lds_bf16_t* smem = (lds_bf16_t*)smem_raw;
   unsigned id = xcd_remap(blockIdx.x, gridDim.x);
   // consecutive ids: row tiles of one column panel, then the next panel, then the next problem,
   // so the tiles sharing a B panel (weights of the matmul) are in flight together on one XCD.
@@ -21,31 +21,41 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
   const int row0 = tm * Cfg::kBM, col0 = tn * Cfg::kBN;
   const int rows_left = a.rows - row0, cols_left = a.cols - col0;
 
-  ATileLoader<Cfg::kBM, ALIGN_A> la;
-  la.base = a.A + z0 * a.sA0 + z1 * a.sA1 + (long)row0 * a.lda;
-  la.lda = a.lda;
-  la.rows_left = rows_left;
-  la.K = a.K;
   const long coff = z0 * a.sC0 + z1 * a.sC1 + (long)row0 * a.ldc + col0;
   bf16_t* C = a.C + coff;
   const bf16_t* R = a.R ? a.R + coff : nullptr;
   const long rvo = z0 * a.ep.row_vec_stride0 + z1 * a.ep.row_vec_stride1 + row0;
   const long cvo = z0 * a.ep.col_vec_stride0 + z1 * a.ep.col_vec_stride1 + col0;
+  const bf16_t* Abase = a.A + z0 * a.sA0 + z1 * a.sA1 + (long)row0 * a.lda;
+  const bf16_t* Bbase = a.B + z0 * a.sB0 + z1 * a.sB1;
   if constexpr (BKIND == 0) {
+    ATileLoader<Cfg::kBM, ALIGN_A, false> la;
+    la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
     BIm2colLoader<Cfg::kBN> lb;
-    lb.xg = a.B + z0 * a.sB0 + z1 * a.sB1;
-    lb.g = a.geom;
-    lb.cols_left = cols_left;
-    lb.K = a.K;
-    lb.col0 = col0;
+    lb.xg = Bbase; lb.g = a.geom; lb.cols_left = cols_left; lb.K = a.K; lb.col0 = col0;
     gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
   } else {
-    BDenseLoader<Cfg::kBN, BKIND> lb;
-    lb.base = a.B + z0 * a.sB0 + z1 * a.sB1 + col0;
-    lb.ldb = a.ldb;
-    lb.cols_left = cols_left;
-    lb.K = a.K;
-    gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
+    auto general = [&]() {
+      ATileLoader<Cfg::kBM, ALIGN_A, false> la;
+      la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
+      BDenseLoader<Cfg::kBN, BKIND == 0 ? 1 : BKIND, false> lb;
+      lb.base = Bbase + col0; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
+      gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
+    };
+    if constexpr (ALIGN_A == 16 && BKIND == 8) {
+      // interior tiles of fully aligned problems run without any predicate in the k loop
+      if (rows_left >= Cfg::kBM && cols_left >= Cfg::kBN && a.K % kBK == 0) {
+        ATileLoader<Cfg::kBM, 16, true> la;
+        la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
+        BDenseLoader<Cfg::kBN, 8, true> lb;
+        lb.base = Bbase + col0; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
+        gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
+      } else {
+        general();
+      }
+    } else {
+      general();
+    }
   }
 }
 

@@ -7,50 +7,71 @@
 //
 // A is row-major with k contiguous (activation rows of the matmul; weight rows of a convolution).
 // B is "k-major": element (k, j) has j contiguous in memory (the matmul's W[K][Nout]; a
-// convolution's input planes, where j runs over output positions).  The MFMA wants 8 consecutive
-// k per lane for BOTH operands, so the B loader transposes 8x8 blocks in registers on the way from
-// HBM to LDS.  Both LDS tiles are then [row][k] with a padded pitch and are read with 16-byte
-// ds_reads that hit distinct banks.
+// convolution's input planes, where j runs over output positions).  Both are copied to LDS in the
+// layout they have in memory -- A tile [BM][64], B tile [64][BN] -- so global loads and LDS stores
+// are plain 16-byte copies.  The MFMA wants 8 consecutive k per lane for both operands: A
+// fragments are 16-byte LDS reads; B fragments use gfx950's transposing LDS read
+// (ds_read_b64_tr_b16), which hands each lane of a 16-lane group 4 consecutive k of one column.
 //
 // Workgroup = 256 threads = 4 wavefronts.  Wave (wm, wn) owns a (BM/WGM) x (BN/WGN) block of the
-// tile, as FM x FN MFMA 32x32x16 accumulators.  K advances in steps of 64 with the next step's
+// tile as FM x FN MFMA 32x32x16 accumulators, computed TRANSPOSED (the instruction's A operand is
+// the B fragment) so that a lane ends up with 4 consecutive output columns of one row: the
+// epilogue can then move 16 bytes at a time.  K advances in steps of 64 with the next step's
 // global loads in flight (registers) while the current one is multiplied out of LDS; LDS is
 // double buffered so one barrier per step suffices.
+//
+// Epilogue: per-row / per-column constants and the activation are applied to the accumulators,
+// which pass through LDS (fp32) to turn the MFMA layout into full rows; each thread then adds
+// the residual (read 16 bytes at a time), rounds once to bf16 and stores 16 bytes.
 #pragma once
 #include "nf_common.h"
 
 namespace nf {
 
-constexpr int kBK = 64;            // k extent of one LDS stage
-constexpr int kPitch = kBK + 8;    // LDS row pitch in elements: 144 B -> 16-B slots rotate by one per row
+// Pointers into LDS carry their address space explicitly: a generic pointer makes the compiler
+// emit flat loads, which count against the global-memory counter too and serialise the prefetch.
+typedef __attribute__((address_space(3))) bf16_t lds_bf16_t;
+typedef __attribute__((address_space(3))) float lds_f32_t;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4v_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x4_t lds_u32x4_t;
+typedef __attribute__((address_space(3))) u32x2_t lds_u32x2_t;
+typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
+typedef __attribute__((address_space(3))) bf16x8_t lds_bf16x8_t;
+typedef __attribute__((address_space(3))) f32x4v_t lds_f32x4_t;
+
+__device__ __forceinline__ void lds_store16(lds_bf16_t* p, uint4 v) { *(lds_u32x4_t*)p = u32x4_t{v.x, v.y, v.z, v.w}; }
+__device__ __forceinline__ void lds_store8(lds_bf16_t* p, uint32_t a, uint32_t b) { *(lds_u32x2_t*)p = u32x2_t{a, b}; }
+
+constexpr int kBK = 64;             // k extent of one LDS stage
+constexpr int kPitchA = kBK + 8;    // A tile row pitch (elements): 144 B, 16-B slots rotate by one per row
+constexpr int kPadB = 16;           // B tile row pitch = BN + 16 elements: pitch mod 128 B = 32 B, so the 4
+                                    // rows touched by one transposing read fall into distinct bank groups
 
 struct Epilogue {
   const float* row_bias;    // [z][i] or null      (convolution bias per output channel)
   const float* row_scale;   // [z][i] or null      (folded batch norm), with row_shift
   const float* row_shift;
   const float* col_bias;    // [z][j] or null      (matmul bias per output feature)
-  const bf16_t* residual;   // addressed like C, or null (C may alias it)
   long row_vec_stride0, row_vec_stride1;   // z = z1 * nz0 + z0 -> offset z0*stride0 + z1*stride1
   long col_vec_stride0, col_vec_stride1;
   int act;
   int act_before_residual;  // matmul: act(.) + residual;  convolution: act(. + residual)
-};
-
-struct GemmShape {
-  int rows, cols, K;        // per-problem extents of C and of the contraction
-  int nz0, nz1;             // batch = nz1 x nz0 problems
-  int tiles_m, tiles_n;
+  int vec_store;            // C (and residual) rows are 16-byte aligned and cols % 8 == 0
 };
 
 // ------------------------------------------------------------------------------------------
-// global -> register loads of 8 consecutive k (one LDS "chunk"), for a given byte alignment
+// A tile loader: [BM][64] from a row-major matrix, 16-byte chunks; chunk c -> row c/8, k-chunk c%8,
+// so 8 neighbouring lanes read and write 128 contiguous bytes.
+// ALIGN = guaranteed byte alignment of every row start (K is then a multiple of ALIGN/2).
+// FULL = the tile lies inside the matrix and K % 64 == 0: no predicates at all (needs ALIGN 16).
 // ------------------------------------------------------------------------------------------
-// ALIGN = guaranteed alignment in bytes of (row start + any multiple of ALIGN/2 elements).
-// Elements at k >= klim read as zero; klim - k is a multiple of ALIGN/2 by the dispatch rules.
 template <int ALIGN>
-__device__ __forceinline__ uint4 load_k8(const bf16_t* p, int k, int klim, bool row_ok) {
+__device__ __forceinline__ uint4 load_k8(const bf16_t* p, int k, int klim) {
   uint4 r = make_uint4(0, 0, 0, 0);
-  if (!row_ok) return r;
   if constexpr (ALIGN == 16) {
     if (k < klim) r = *reinterpret_cast<const uint4*>(p);
   } else if constexpr (ALIGN == 8) {
@@ -58,11 +79,6 @@ __device__ __forceinline__ uint4 load_k8(const bf16_t* p, int k, int klim, bool 
     if (k < klim) a = *reinterpret_cast<const uint2*>(p);
     if (k + 4 < klim) b = *reinterpret_cast<const uint2*>(p + 4);
     r = make_uint4(a.x, a.y, b.x, b.y);
-  } else if constexpr (ALIGN == 4) {
-    uint32_t w[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) w[e] = (k + 2 * e < klim) ? *reinterpret_cast<const uint32_t*>(p + 2 * e) : 0u;
-    r = make_uint4(w[0], w[1], w[2], w[3]);
   } else {
     uint32_t h[8];
 #pragma unroll
@@ -72,12 +88,11 @@ __device__ __forceinline__ uint4 load_k8(const bf16_t* p, int k, int klim, bool 
   return r;
 }
 
-// Loader of the A tile [BM][64]: chunk c -> row c/8, k-chunk c%8, so 8 neighbouring lanes read and
-// write 128 contiguous bytes.
-template <int BM, int ALIGN>
+template <int BM, int ALIGN, bool FULL>
 struct ATileLoader {
   static constexpr int kChunks = BM * (kBK / 8);
   static constexpr int kPer = (kChunks + 255) / 256;
+  static_assert(kChunks % 256 == 0, "tile too small for 256 threads");
   const bf16_t* base;   // A + problem offset + row0*lda
   long lda;
   int rows_left;        // rows of the problem from row0 on
@@ -89,85 +104,65 @@ struct ATileLoader {
     for (int t = 0; t < kPer; ++t) {
       const int c = tid + t * 256;
       const int r = c / 8, kc = (c % 8) * 8;
-      const bool ok = (kChunks % 256 == 0 || c < kChunks) && r < rows_left;
-      regs[t] = load_k8<ALIGN>(base + (long)r * lda + k0 + kc, k0 + kc, K, ok);
+      if constexpr (FULL) {
+        regs[t] = *reinterpret_cast<const uint4*>(base + (long)r * lda + k0 + kc);
+      } else {
+        regs[t] = r < rows_left ? load_k8<ALIGN>(base + (long)r * lda + k0 + kc, k0 + kc, K) : make_uint4(0, 0, 0, 0);
+      }
     }
   }
-  __device__ __forceinline__ void commit(bf16_t* lds, int tid) const {
+  __device__ __forceinline__ void commit(lds_bf16_t* lds, int tid) const {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
       const int c = tid + t * 256;
-      if (kChunks % 256 == 0 || c < kChunks) {
-        const int r = c / 8, kc = (c % 8) * 8;
-        *reinterpret_cast<uint4*>(lds + r * kPitch + kc) = regs[t];
-      }
+      lds_store16(lds + (c / 8) * kPitchA + (c % 8) * 8, regs[t]);
     }
   }
 };
 
-// 8 (k) x VEC (j) block held as 8 rows of VEC/2 dwords -> VEC vectors of 8 consecutive k.
-template <int VEC>
-__device__ __forceinline__ void transpose_k8(const uint32_t (&in)[8][(VEC + 1) / 2], uint4 (&out)[VEC]) {
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) {
-    uint32_t w[4];
-#pragma unroll
-    for (int kp = 0; kp < 4; ++kp) {
-      const uint32_t lo = in[2 * kp][e / 2], hi = in[2 * kp + 1][e / 2];
-      w[kp] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
-    }
-    out[e] = make_uint4(w[0], w[1], w[2], w[3]);
-  }
-}
-
-// Loader of the B tile from a dense k-major matrix B[k][j] (j contiguous, row pitch ldb):
-// task t -> k-block t%8 (8 consecutive k) and j-chunk t/8 (VEC consecutive j).  8 neighbouring
-// lanes read the same j-chunk of 8 row groups and, after the register transpose, write 128
-// contiguous bytes of one LDS row.  VEC = 8 / 4 / 1 needs 16 / 8 / 2-byte aligned rows.
-template <int BN, int VEC>
+// ------------------------------------------------------------------------------------------
+// B tile loader, dense k-major matrix B[k][j] (row pitch ldb): [64][BN] copied as is.
+// VEC = 8 / 4 / 1 elements per access (16 / 8 / 2-byte aligned rows; cols % VEC == 0).
+// ------------------------------------------------------------------------------------------
+template <int BN, int VEC, bool FULL>
 struct BDenseLoader {
-  static constexpr int kTasks = (kBK / 8) * (BN / VEC);
-  static constexpr int kPer = (kTasks + 255) / 256;
-  static constexpr int kDw = (VEC + 1) / 2;
+  static constexpr int kPitch = BN + kPadB;
+  static constexpr int kPerRow = BN / VEC;
+  static constexpr int kTasks = kBK * kPerRow;
+  static constexpr int kPer = kTasks / 256;
+  static_assert(kTasks % 256 == 0, "tile too small for 256 threads");
+  static constexpr int kDw = VEC == 8 ? 4 : (VEC == 4 ? 2 : 1);
   const bf16_t* base;   // B + problem offset + col0
   long ldb;
   int cols_left, K;
-  uint32_t regs[kPer][8][kDw];
+  uint32_t regs[kPer][kDw];
 
   __device__ __forceinline__ void fetch(int k0, int tid) {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
       const int task = tid + t * 256;
-      const int kb = (task % 8) * 8, j = (task / 8) * VEC;
-      const bool ok = (kTasks % 256 == 0 || task < kTasks) && j < cols_left;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const int k = k0 + kb + r;
-        const bf16_t* p = base + (long)k * ldb + j;
-        const bool live = ok && k < K;
-        if constexpr (VEC == 8) {
-          const uint4 v = live ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
-          regs[t][r][0] = v.x; regs[t][r][1] = v.y; regs[t][r][2] = v.z; regs[t][r][3] = v.w;
-        } else if constexpr (VEC == 4) {
-          const uint2 v = live ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
-          regs[t][r][0] = v.x; regs[t][r][1] = v.y;
-        } else {
-          regs[t][r][0] = live ? (uint32_t)*p : 0u;
-        }
+      const int k = k0 + task / kPerRow, j = (task % kPerRow) * VEC;
+      const bf16_t* p = base + (long)k * ldb + j;
+      const bool live = FULL || (k < K && j < cols_left);
+      if constexpr (VEC == 8) {
+        const uint4 v = live ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+        regs[t][0] = v.x; regs[t][1] = v.y; regs[t][2] = v.z; regs[t][3] = v.w;
+      } else if constexpr (VEC == 4) {
+        const uint2 v = live ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
+        regs[t][0] = v.x; regs[t][1] = v.y;
+      } else {
+        regs[t][0] = live ? (uint32_t)*p : 0u;
       }
     }
   }
-  __device__ __forceinline__ void commit(bf16_t* lds, int tid) const {
+  __device__ __forceinline__ void commit(lds_bf16_t* lds, int tid) const {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
       const int task = tid + t * 256;
-      if (kTasks % 256 == 0 || task < kTasks) {
-        const int kb = (task % 8) * 8, j = (task / 8) * VEC;
-        uint4 out[VEC];
-        transpose_k8<VEC>(regs[t], out);
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) *reinterpret_cast<uint4*>(lds + (j + e) * kPitch + kb) = out[e];
-      }
+      lds_bf16_t* dst = lds + (task / kPerRow) * kPitch + (task % kPerRow) * VEC;
+      if constexpr (VEC == 8) lds_store16(dst, make_uint4(regs[t][0], regs[t][1], regs[t][2], regs[t][3]));
+      else if constexpr (VEC == 4) lds_store8(dst, regs[t][0], regs[t][1]);
+      else *dst = (bf16_t)regs[t][0];
     }
   }
 };
@@ -179,13 +174,15 @@ struct Im2colGeom {
   int H, W, KH, KW, Wo, stride, pad, dil;
 };
 
-// Loader of the B tile gathered from the input planes: same task shape as the dense loader with
-// VEC = 1 (one output position, 8 consecutive k), element-wise loads with bounds checks.
+// B tile loader gathering from the input planes: task = one k row x 8 consecutive output positions
+// (consecutive ox of one output row read consecutive-or-strided input pixels of one input row).
 template <int BN>
 struct BIm2colLoader {
-  static constexpr int kTasks = (kBK / 8) * BN;
+  static constexpr int kPitch = BN + kPadB;
+  static constexpr int kPerRow = BN / 8;
+  static constexpr int kTasks = kBK * kPerRow;
   static constexpr int kPer = kTasks / 256;
-  static_assert(kTasks % 256 == 0, "tile too small");
+  static_assert(kTasks % 256 == 0, "tile too small for 256 threads");
   const bf16_t* xg;     // first input plane of this group and image
   Im2colGeom g;
   int cols_left, K, col0;
@@ -196,35 +193,31 @@ struct BIm2colLoader {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
       const int task = tid + t * 256;
-      const int kb = (task % 8) * 8, j = task / 8;
+      const int k = k0 + task / kPerRow, j = (task % kPerRow) * 8;
       uint32_t h[8];
-      if (j < cols_left) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) h[e] = 0u;
+      if (k < K && j < cols_left) {
+        const int ci = k / khw, rem = k - ci * khw;
+        const int ky = rem / g.KW, kx = rem - ky * g.KW;
+        const bf16_t* plane = xg + (long)ci * g.H * g.W;
         const int p = col0 + j;
-        const int oy = p / g.Wo, ox = p - oy * g.Wo;
-        const int iy0 = oy * g.stride - g.pad, ix0 = ox * g.stride - g.pad;
-        int k = k0 + kb;
-        int ci = k / khw, rem = k - ci * khw;
-        int ky = rem / g.KW, kx = rem - ky * g.KW;
+        int oy = p / g.Wo, ox = p - oy * g.Wo;
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          const int iy = iy0 + ky * g.dil, ix = ix0 + kx * g.dil;
-          const bool live = (k + r) < K && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W;
-          h[r] = live ? (uint32_t)xg[((long)ci * g.H + iy) * g.W + ix] : 0u;
-          if (++kx == g.KW) { kx = 0; if (++ky == g.KH) { ky = 0; ++ci; } }
+        for (int e = 0; e < 8; ++e) {
+          const int iy = oy * g.stride - g.pad + ky * g.dil, ix = ox * g.stride - g.pad + kx * g.dil;
+          if (j + e < cols_left && iy >= 0 && iy < g.H && ix >= 0 && ix < g.W) h[e] = (uint32_t)plane[(long)iy * g.W + ix];
+          if (++ox == g.Wo) { ox = 0; ++oy; }
         }
-      } else {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) h[r] = 0u;
       }
       regs[t] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
     }
   }
-  __device__ __forceinline__ void commit(bf16_t* lds, int tid) const {
+  __device__ __forceinline__ void commit(lds_bf16_t* lds, int tid) const {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
       const int task = tid + t * 256;
-      const int kb = (task % 8) * 8, j = task / 8;
-      *reinterpret_cast<uint4*>(lds + j * kPitch + kb) = regs[t];
+      lds_store16(lds + (task / kPerRow) * kPitch + (task % kPerRow) * 8, regs[t]);
     }
   }
 };
@@ -239,21 +232,28 @@ struct TileCfg {
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int FM = WM / 32, FN = WN / 32;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
-  static constexpr int kLdsA = BM * kPitch, kLdsB = BN * kPitch;          // elements per stage
-  static constexpr int kLdsBytes = 2 * (kLdsA + kLdsB) * (int)sizeof(bf16_t);
+  static constexpr int kPitchB = BN + kPadB;
+  static constexpr int kLdsA = BM * kPitchA, kLdsB = kBK * kPitchB;       // elements per stage
+  static constexpr int kLdsPipe = 2 * (kLdsA + kLdsB) * (int)sizeof(bf16_t);
+  // epilogue staging: one 32-row block of every wave row at a time, fp32, padded rows
+  static constexpr int kEpiPitch = BN + 4;
+  static constexpr int kLdsEpi = WGM * 32 * kEpiPitch * (int)sizeof(float);
+  static constexpr int kLdsBytes = kLdsPipe > kLdsEpi ? kLdsPipe : kLdsEpi;
 };
 
 template <class Cfg, class ALoader, class BLoader>
-__device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, bf16_t* smem,
+__device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_bf16_t* smem,
                                           bf16_t* C, const bf16_t* R, long ldc, int rows_left,
                                           int cols_left, const Epilogue& ep, long row_vec_off,
                                           long col_vec_off) {
   constexpr int FM = Cfg::FM, FN = Cfg::FN;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;   // this wave's block of the tile
-  bf16_t* As[2] = {smem, smem + Cfg::kLdsA};
-  bf16_t* Bs[2] = {smem + 2 * Cfg::kLdsA, smem + 2 * Cfg::kLdsA + Cfg::kLdsB};
+  lds_bf16_t* const As = smem;                       // stage s of A at As + s * kLdsA
+  lds_bf16_t* const Bs = smem + 2 * Cfg::kLdsA;      // stage s of B at Bs + s * kLdsB
 
+  // acc[i][j]: rows wm*WM + 32 i .. of C, columns wn*WN + 32 j ..; held transposed:
+  // register r of lane l is row (l % 32), column 8 (r/4) + 4 (l/32) + r % 4 of the 32x32 block.
   f32x16_t acc[FM][FN];
 #pragma unroll
   for (int i = 0; i < FM; ++i)
@@ -265,68 +265,122 @@ __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, bf16_
   const int nk = (K + kBK - 1) / kBK;
   la.fetch(0, tid);
   lb.fetch(0, tid);
-  la.commit(As[0], tid);
-  lb.commit(Bs[0], tid);
+  la.commit(As, tid);
+  lb.commit(Bs, tid);
   __syncthreads();
 
-  // lane -> MFMA operand slice: row (lane % 32) of the 32-row block, k offset 8 * (lane / 32)
-  const int frag_row = lane % 32, frag_k = (lane / 32) * 8;
+  // A fragment of lane l: row l % 32 of a 32-row block, k = 8 (l/32) .. + 7 of a 16-step.
+  // B fragment of lane l: column l % 32 of a 32-column block, same k; fetched as two transposing
+  // reads of 4 k each.  In a 16-lane group, lane i points at row (i/4), columns 4 (i%4) .. + 3 of
+  // the 4 x 16 block the group transposes, and receives the 4 rows of column i.
+  const int half = lane / 32, l32 = lane % 32, l16 = lane % 16;
+  const int a_off = (wm * Cfg::WM + l32) * kPitchA + half * 8;
+  const int b_off = (half * 8 + l16 / 4) * Cfg::kPitchB + wn * Cfg::WN + ((lane / 16) % 2) * 16 + (l16 % 4) * 4;
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < nk) {
       la.fetch((kt + 1) * kBK, tid);
       lb.fetch((kt + 1) * kBK, tid);
     }
-    const bf16_t* a_lds = As[cur] + (wm * Cfg::WM + frag_row) * kPitch + frag_k;
-    const bf16_t* b_lds = Bs[cur] + (wn * Cfg::WN + frag_row) * kPitch + frag_k;
+    const lds_bf16_t* a_lds = As + cur * Cfg::kLdsA + a_off;
+    const lds_bf16_t* b_lds = Bs + cur * Cfg::kLdsB + b_off;
 #pragma unroll
     for (int kk = 0; kk < kBK / 16; ++kk) {
       bf16x8_t af[FM], bfr[FN];
 #pragma unroll
-      for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8_t*>(a_lds + i * 32 * kPitch + kk * 16);
+      for (int i = 0; i < FM; ++i) af[i] = *(const lds_bf16x8_t*)(a_lds + i * 32 * kPitchA + kk * 16);
 #pragma unroll
-      for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8_t*>(b_lds + j * 32 * kPitch + kk * 16);
+      for (int j = 0; j < FN; ++j) {
+        const lds_bf16_t* p = b_lds + kk * 16 * Cfg::kPitchB + j * 32;
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)p);
+        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(p + 4 * Cfg::kPitchB));
+        const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        bfr[j] = __builtin_bit_cast(bf16x8_t, both);
+      }
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) {
-      la.commit(As[cur ^ 1], tid);
-      lb.commit(Bs[cur ^ 1], tid);
+      la.commit(As + (cur ^ 1) * Cfg::kLdsA, tid);
+      lb.commit(Bs + (cur ^ 1) * Cfg::kLdsB, tid);
     }
     __syncthreads();
   }
 
-  // Epilogue.  Accumulator register r of a 32x32 block holds row 8*(r/4) + 4*(lane/32) + r%4,
-  // column lane%32.
-  const int col_in = lane % 32, row_in = (lane / 32) * 4;
+  // ---- epilogue, one 32-row block of each wave row per pass
+  lds_f32_t* const Es = (lds_f32_t*)smem;
+  constexpr int kEP = Cfg::kEpiPitch;
+  constexpr int kChunksPerRow = Cfg::kBN / 8;
+  constexpr int kPassChunks = Cfg::kWGM * 32 * kChunksPerRow;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
+    {
+      const int row = wm * Cfg::WM + i * 32 + l32;           // this lane's row in the tile
+      float rb = 0.f, rs = 1.f, rt = 0.f;
+      if (row < rows_left) {
+        if (ep.row_bias) rb = ep.row_bias[row_vec_off + row];
+        if (ep.row_scale) { rs = ep.row_scale[row_vec_off + row]; rt = ep.row_shift[row_vec_off + row]; }
+      }
+      lds_f32_t* erow = Es + (wm * 32 + l32) * kEP + wn * Cfg::WN + half * 4;
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-      const int col = wn * Cfg::WN + j * 32 + col_in;
-      if (col >= cols_left) continue;
-      const float cb = ep.col_bias ? ep.col_bias[col_vec_off + col] : 0.f;
+      for (int j = 0; j < FN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = wm * Cfg::WM + i * 32 + 8 * (r / 4) + row_in + (r % 4);
-        if (row >= rows_left) continue;
-        float v = acc[i][j][r] + cb;
-        if (ep.row_bias) v += ep.row_bias[row_vec_off + row];
-        if (ep.row_scale) v = fmaf(v, ep.row_scale[row_vec_off + row], ep.row_shift[row_vec_off + row]);
-        const long o = (long)row * ldc + col;
-        if (ep.act_before_residual) {
-          v = apply_act(v, ep.act);
-          if (R) v += bf16_to_f32(R[o]);
-        } else {
-          if (R) v += bf16_to_f32(R[o]);
-          v = apply_act(v, ep.act);
+        for (int q = 0; q < 4; ++q) {
+          const int col = wn * Cfg::WN + j * 32 + q * 8 + half * 4;
+          f32x4v_t v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float t = acc[i][j][q * 4 + e];
+            if (ep.col_bias) t += (col + e < cols_left) ? ep.col_bias[col_vec_off + col + e] : 0.f;
+            t = fmaf(t + rb, rs, rt);
+            if (ep.act_before_residual) t = apply_act(t, ep.act);
+            v[e] = t;
+          }
+          *(lds_f32x4_t*)(erow + j * 32 + q * 8) = v;
         }
-        C[o] = f32_to_bf16(v);
+    }
+    __syncthreads();
+    for (int c = tid; c < kPassChunks; c += 256) {
+      const int prow = c / kChunksPerRow, col = (c % kChunksPerRow) * 8;
+      const int row = (prow / 32) * Cfg::WM + i * 32 + (prow % 32);
+      if (row >= rows_left || col >= cols_left) continue;
+      const lds_f32_t* src = Es + prow * kEP + col;
+      const f32x4v_t v0 = *(const lds_f32x4_t*)src, v1 = *(const lds_f32x4_t*)(src + 4);
+      float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+      const long o = (long)row * ldc + col;
+      if (ep.vec_store) {
+        if (R) {
+          const uint4 rr = *reinterpret_cast<const uint4*>(R + o);
+          const uint32_t w[4] = {rr.x, rr.y, rr.z, rr.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[2 * e] += __uint_as_float(w[e] << 16);
+            v[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+          }
+        }
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float a0 = v[2 * e], a1 = v[2 * e + 1];
+          if (!ep.act_before_residual) { a0 = apply_act(a0, ep.act); a1 = apply_act(a1, ep.act); }
+          w[e] = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
+        }
+        *reinterpret_cast<uint4*>(C + o) = make_uint4(w[0], w[1], w[2], w[3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (col + e >= cols_left) break;
+          float t = v[e];
+          if (R) t += bf16_to_f32(R[o + e]);
+          if (!ep.act_before_residual) t = apply_act(t, ep.act);
+          C[o + e] = f32_to_bf16(t);
+        }
       }
     }
+    __syncthreads();
   }
 }
 

@@ -137,6 +137,7 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     L.nz1 = 1;
     a.ep.col_bias = bias; a.ep.col_vec_stride0 = Nout;
     a.ep.act = act; a.ep.act_before_residual = 1;
+    a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16);
     return launch_gemm_any(bkind, al, pick_tile(N, Nout, M), L, s);
   }
   const int tiles_m = (N + 63) / 64, tiles_n = (Nout + 63) / 64;
@@ -194,6 +195,7 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     a.ep.row_bias = bias; a.ep.row_scale = scale; a.ep.row_shift = shift;
     a.ep.row_vec_stride0 = cog; a.ep.row_vec_stride1 = 0;
     a.ep.act = act; a.ep.act_before_residual = 0;
+    a.ep.vec_store = HoWo % 8 == 0 && aligned(y, 16) && aligned(residual, 16);
     int al = common_align({w}, {Kdim});
     while (al > 2 && (Kdim % (al / 2)) != 0) al /= 2;
     const long long problems = (long long)M * g * B;
