@@ -8,7 +8,7 @@
 namespace nf {
 
 template <class Cfg, int ALIGN_A, int BKIND>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
+__global__ __launch_bounds__(Cfg::kThreads) void gemm_mfma_kernel(GemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   lds_bf16_t* smem = (lds_bf16_t*)smem_raw;
   unsigned id = xcd_remap(blockIdx.x, gridDim.x);
@@ -29,25 +29,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs a) {
   const bf16_t* Abase = a.A + z0 * a.sA0 + z1 * a.sA1 + (long)row0 * a.lda;
   const bf16_t* Bbase = a.B + z0 * a.sB0 + z1 * a.sB1;
   if constexpr (BKIND == 0) {
-    ATileLoader<Cfg::kBM, ALIGN_A, false> la;
+    ATileLoader<Cfg::kBM, ALIGN_A, false, Cfg::kThreads> la;
     la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
-    BIm2colLoader<Cfg::kBN> lb;
+    BIm2colLoader<Cfg::kBN, Cfg::kThreads> lb;
     lb.xg = Bbase; lb.g = a.geom; lb.cols_left = cols_left; lb.K = a.K; lb.col0 = col0;
     gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
   } else {
     auto general = [&]() {
-      ATileLoader<Cfg::kBM, ALIGN_A, false> la;
+      ATileLoader<Cfg::kBM, ALIGN_A, false, Cfg::kThreads> la;
       la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
-      BDenseLoader<Cfg::kBN, BKIND == 0 ? 1 : BKIND, false> lb;
+      BDenseLoader<Cfg::kBN, BKIND == 0 ? 1 : BKIND, false, Cfg::kThreads> lb;
       lb.base = Bbase + col0; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
       gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
     };
     if constexpr (ALIGN_A == 16 && BKIND == 8) {
       // interior tiles of fully aligned problems run without any predicate in the k loop
       if (rows_left >= Cfg::kBM && cols_left >= Cfg::kBN && a.K % kBK == 0) {
-        ATileLoader<Cfg::kBM, 16, true> la;
+        ATileLoader<Cfg::kBM, 16, true, Cfg::kThreads> la;
         la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
-        BDenseLoader<Cfg::kBN, 8, true> lb;
+        BDenseLoader<Cfg::kBN, 8, true, Cfg::kThreads> lb;
         lb.base = Bbase + col0; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
         gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
       } else {
@@ -77,7 +77,7 @@ nf_status launch_gemm(GemmLaunch& L, hipStream_t s) {
       opted_in.store(true, std::memory_order_release);
     }
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(256), Cfg::kLdsBytes, s, a);
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(Cfg::kThreads), Cfg::kLdsBytes, s, a);
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
 }
 
@@ -90,6 +90,9 @@ nf_status launch_gemm_tile(int tile, GemmLaunch& L, hipStream_t s) {
     case T64x128: return launch_gemm<TileCfg<64, 128, 2, 2>, ALIGN_A, BKIND>(L, s);
     case T64x64: return launch_gemm<TileCfg<64, 64, 2, 2>, ALIGN_A, BKIND>(L, s);
     case T32x128: return launch_gemm<TileCfg<32, 128, 1, 4>, ALIGN_A, BKIND>(L, s);
+    case T256x256w8: return launch_gemm<TileCfg<256, 256, 2, 4>, ALIGN_A, BKIND>(L, s);
+    case T128x256w8: return launch_gemm<TileCfg<128, 256, 2, 4>, ALIGN_A, BKIND>(L, s);
+    case T128x128w8: return launch_gemm<TileCfg<128, 128, 2, 4>, ALIGN_A, BKIND>(L, s);
   }
   return NF_EUNSUPPORTED;
 }

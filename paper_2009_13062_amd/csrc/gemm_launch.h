@@ -23,9 +23,9 @@ struct GemmLaunch {
   int nz1;
 };
 
-enum TileId { T128x128 = 0, T128x256, T256x128, T64x128, T64x64, T32x128, kNumTiles };
-constexpr int kTileBM[kNumTiles] = {128, 128, 256, 64, 64, 32};
-constexpr int kTileBN[kNumTiles] = {128, 256, 128, 128, 64, 128};
+enum TileId { T128x128 = 0, T128x256, T256x128, T64x128, T64x64, T32x128, T256x256w8, T128x256w8, T128x128w8, kNumTiles };
+constexpr int kTileBM[kNumTiles] = {128, 128, 256, 64, 64, 32, 256, 128, 128};
+constexpr int kTileBN[kNumTiles] = {128, 256, 128, 128, 64, 128, 256, 256, 128};
 
 // BKIND: 8 / 4 / 1 = dense B read with that vector width; 0 = implicit (im2col) B.
 // align_a: 16, 8, 4 or 2 = byte alignment of every A row start (and K a multiple of align_a/2).

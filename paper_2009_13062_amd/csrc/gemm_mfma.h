@@ -13,7 +13,7 @@
 // fragments are 16-byte LDS reads; B fragments use gfx950's transposing LDS read
 // (ds_read_b64_tr_b16), which hands each lane of a 16-lane group 4 consecutive k of one column.
 //
-// Workgroup = 256 threads = 4 wavefronts.  Wave (wm, wn) owns a (BM/WGM) x (BN/WGN) block of the
+// Workgroup = 4 or 8 wavefronts.  Wave (wm, wn) owns a (BM/WGM) x (BN/WGN) block of the
 // tile as FM x FN MFMA 32x32x16 accumulators, computed TRANSPOSED (the instruction's A operand is
 // the B fragment) so that a lane ends up with 4 consecutive output columns of one row: the
 // epilogue can then move 16 bytes at a time.  K advances in steps of 64 with the next step's
@@ -88,34 +88,34 @@ __device__ __forceinline__ uint4 load_k8(const bf16_t* p, int k, int klim) {
   return r;
 }
 
-template <int BM, int ALIGN, bool FULL>
+template <int BM, int ALIGN, bool FULL, int NT>
 struct ATileLoader {
   static constexpr int kChunks = BM * (kBK / 8);
-  static constexpr int kPer = (kChunks + 255) / 256;
-  static_assert(kChunks % 256 == 0, "tile too small for 256 threads");
+  static constexpr int kPer = kChunks / NT;
+  static_assert(kChunks % NT == 0, "tile too small for the workgroup");
   const bf16_t* base;   // A + problem offset + row0*lda
   long lda;
   int rows_left;        // rows of the problem from row0 on
   int K;
-  uint4 regs[kPer];
+  struct Regs { uint4 v[kPer]; };     // one k-step of this thread's share, in flight or landed
 
-  __device__ __forceinline__ void fetch(int k0, int tid) {
+  __device__ __forceinline__ void fetch(Regs& regs, int k0, int tid) const {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
-      const int c = tid + t * 256;
+      const int c = tid + t * NT;
       const int r = c / 8, kc = (c % 8) * 8;
       if constexpr (FULL) {
-        regs[t] = *reinterpret_cast<const uint4*>(base + (long)r * lda + k0 + kc);
+        regs.v[t] = *reinterpret_cast<const uint4*>(base + (long)r * lda + k0 + kc);
       } else {
-        regs[t] = r < rows_left ? load_k8<ALIGN>(base + (long)r * lda + k0 + kc, k0 + kc, K) : make_uint4(0, 0, 0, 0);
+        regs.v[t] = r < rows_left ? load_k8<ALIGN>(base + (long)r * lda + k0 + kc, k0 + kc, K) : make_uint4(0, 0, 0, 0);
       }
     }
   }
-  __device__ __forceinline__ void commit(lds_bf16_t* lds, int tid) const {
+  __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int tid) const {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
-      const int c = tid + t * 256;
-      lds_store16(lds + (c / 8) * kPitchA + (c % 8) * 8, regs[t]);
+      const int c = tid + t * NT;
+      lds_store16(lds + (c / 8) * kPitchA + (c % 8) * 8, regs.v[t]);
     }
   }
 };
@@ -124,45 +124,45 @@ struct ATileLoader {
 // B tile loader, dense k-major matrix B[k][j] (row pitch ldb): [64][BN] copied as is.
 // VEC = 8 / 4 / 1 elements per access (16 / 8 / 2-byte aligned rows; cols % VEC == 0).
 // ------------------------------------------------------------------------------------------
-template <int BN, int VEC, bool FULL>
+template <int BN, int VEC, bool FULL, int NT>
 struct BDenseLoader {
   static constexpr int kPitch = BN + kPadB;
   static constexpr int kPerRow = BN / VEC;
   static constexpr int kTasks = kBK * kPerRow;
-  static constexpr int kPer = kTasks / 256;
-  static_assert(kTasks % 256 == 0, "tile too small for 256 threads");
+  static constexpr int kPer = kTasks / NT;
+  static_assert(kTasks % NT == 0, "tile too small for the workgroup");
   static constexpr int kDw = VEC == 8 ? 4 : (VEC == 4 ? 2 : 1);
   const bf16_t* base;   // B + problem offset + col0
   long ldb;
   int cols_left, K;
-  uint32_t regs[kPer][kDw];
+  struct Regs { uint32_t v[kPer][kDw]; };
 
-  __device__ __forceinline__ void fetch(int k0, int tid) {
+  __device__ __forceinline__ void fetch(Regs& regs, int k0, int tid) const {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
-      const int task = tid + t * 256;
+      const int task = tid + t * NT;
       const int k = k0 + task / kPerRow, j = (task % kPerRow) * VEC;
       const bf16_t* p = base + (long)k * ldb + j;
       const bool live = FULL || (k < K && j < cols_left);
       if constexpr (VEC == 8) {
         const uint4 v = live ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
-        regs[t][0] = v.x; regs[t][1] = v.y; regs[t][2] = v.z; regs[t][3] = v.w;
+        regs.v[t][0] = v.x; regs.v[t][1] = v.y; regs.v[t][2] = v.z; regs.v[t][3] = v.w;
       } else if constexpr (VEC == 4) {
         const uint2 v = live ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
-        regs[t][0] = v.x; regs[t][1] = v.y;
+        regs.v[t][0] = v.x; regs.v[t][1] = v.y;
       } else {
-        regs[t][0] = live ? (uint32_t)*p : 0u;
+        regs.v[t][0] = live ? (uint32_t)*p : 0u;
       }
     }
   }
-  __device__ __forceinline__ void commit(lds_bf16_t* lds, int tid) const {
+  __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int tid) const {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
-      const int task = tid + t * 256;
+      const int task = tid + t * NT;
       lds_bf16_t* dst = lds + (task / kPerRow) * kPitch + (task % kPerRow) * VEC;
-      if constexpr (VEC == 8) lds_store16(dst, make_uint4(regs[t][0], regs[t][1], regs[t][2], regs[t][3]));
-      else if constexpr (VEC == 4) lds_store8(dst, regs[t][0], regs[t][1]);
-      else *dst = (bf16_t)regs[t][0];
+      if constexpr (VEC == 8) lds_store16(dst, make_uint4(regs.v[t][0], regs.v[t][1], regs.v[t][2], regs.v[t][3]));
+      else if constexpr (VEC == 4) lds_store8(dst, regs.v[t][0], regs.v[t][1]);
+      else *dst = (bf16_t)regs.v[t][0];
     }
   }
 };
@@ -176,23 +176,23 @@ struct Im2colGeom {
 
 // B tile loader gathering from the input planes: task = one k row x 8 consecutive output positions
 // (consecutive ox of one output row read consecutive-or-strided input pixels of one input row).
-template <int BN>
+template <int BN, int NT>
 struct BIm2colLoader {
   static constexpr int kPitch = BN + kPadB;
   static constexpr int kPerRow = BN / 8;
   static constexpr int kTasks = kBK * kPerRow;
-  static constexpr int kPer = kTasks / 256;
-  static_assert(kTasks % 256 == 0, "tile too small for 256 threads");
+  static constexpr int kPer = kTasks / NT;
+  static_assert(kTasks % NT == 0, "tile too small for the workgroup");
   const bf16_t* xg;     // first input plane of this group and image
   Im2colGeom g;
   int cols_left, K, col0;
-  uint4 regs[kPer];
+  struct Regs { uint4 v[kPer]; };
 
-  __device__ __forceinline__ void fetch(int k0, int tid) {
+  __device__ __forceinline__ void fetch(Regs& regs, int k0, int tid) const {
     const int khw = g.KH * g.KW;
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
-      const int task = tid + t * 256;
+      const int task = tid + t * NT;
       const int k = k0 + task / kPerRow, j = (task % kPerRow) * 8;
       uint32_t h[8];
 #pragma unroll
@@ -210,14 +210,14 @@ struct BIm2colLoader {
           if (++ox == g.Wo) { ox = 0; ++oy; }
         }
       }
-      regs[t] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+      regs.v[t] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
     }
   }
-  __device__ __forceinline__ void commit(lds_bf16_t* lds, int tid) const {
+  __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int tid) const {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
-      const int task = tid + t * 256;
-      lds_store16(lds + (task / kPerRow) * kPitch + (task % kPerRow) * 8, regs[t]);
+      const int task = tid + t * NT;
+      lds_store16(lds + (task / kPerRow) * kPitch + (task % kPerRow) * 8, regs.v[t]);
     }
   }
 };
@@ -227,8 +227,9 @@ struct BIm2colLoader {
 // ------------------------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN>
 struct TileCfg {
-  static_assert(WGM * WGN == 4, "4 wavefronts per workgroup");
+  static_assert(WGM * WGN == 4 || WGM * WGN == 8, "4 or 8 wavefronts per workgroup");
   static constexpr int kBM = BM, kBN = BN, kWGM = WGM, kWGN = WGN;
+  static constexpr int kThreads = WGM * WGN * kWave;
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int FM = WM / 32, FN = WN / 32;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
@@ -262,13 +263,6 @@ __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_b
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = (K + kBK - 1) / kBK;
-  la.fetch(0, tid);
-  lb.fetch(0, tid);
-  la.commit(As, tid);
-  lb.commit(Bs, tid);
-  __syncthreads();
-
   // A fragment of lane l: row l % 32 of a 32-row block, k = 8 (l/32) .. + 7 of a 16-step.
   // B fragment of lane l: column l % 32 of a 32-column block, same k; fetched as two transposing
   // reads of 4 k each.  In a 16-lane group, lane i points at row (i/4), columns 4 (i%4) .. + 3 of
@@ -276,14 +270,10 @@ __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_b
   const int half = lane / 32, l32 = lane % 32, l16 = lane % 16;
   const int a_off = (wm * Cfg::WM + l32) * kPitchA + half * 8;
   const int b_off = (half * 8 + l16 / 4) * Cfg::kPitchB + wn * Cfg::WN + ((lane / 16) % 2) * 16 + (l16 % 4) * 4;
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) {
-      la.fetch((kt + 1) * kBK, tid);
-      lb.fetch((kt + 1) * kBK, tid);
-    }
-    const lds_bf16_t* a_lds = As + cur * Cfg::kLdsA + a_off;
-    const lds_bf16_t* b_lds = Bs + cur * Cfg::kLdsB + b_off;
+
+  auto multiply_stage = [&](int stage) {
+    const lds_bf16_t* a_lds = As + stage * Cfg::kLdsA + a_off;
+    const lds_bf16_t* b_lds = Bs + stage * Cfg::kLdsB + b_off;
 #pragma unroll
     for (int kk = 0; kk < kBK / 16; ++kk) {
       bf16x8_t af[FM], bfr[FN];
@@ -303,9 +293,28 @@ __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_b
         for (int j = 0; j < FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
     }
+  };
+
+  // Software pipeline: while k-step kt is multiplied out of LDS stage kt % 2, the global loads of
+  // step kt+1 are in flight into registers; they are committed to the other stage afterwards.
+  const int nk = (K + kBK - 1) / kBK;
+  typename ALoader::Regs ra;
+  typename BLoader::Regs rb;
+  la.fetch(ra, 0, tid);
+  lb.fetch(rb, 0, tid);
+  la.commit(ra, As, tid);
+  lb.commit(rb, Bs, tid);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
     if (kt + 1 < nk) {
-      la.commit(As + (cur ^ 1) * Cfg::kLdsA, tid);
-      lb.commit(Bs + (cur ^ 1) * Cfg::kLdsB, tid);
+      la.fetch(ra, (kt + 1) * kBK, tid);
+      lb.fetch(rb, (kt + 1) * kBK, tid);
+    }
+    multiply_stage(cur);
+    if (kt + 1 < nk) {
+      la.commit(ra, As + (cur ^ 1) * Cfg::kLdsA, tid);
+      lb.commit(rb, Bs + (cur ^ 1) * Cfg::kLdsB, tid);
     }
     __syncthreads();
   }
@@ -343,7 +352,7 @@ __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_b
         }
     }
     __syncthreads();
-    for (int c = tid; c < kPassChunks; c += 256) {
+    for (int c = tid; c < kPassChunks; c += Cfg::kThreads) {
       const int prow = c / kChunksPerRow, col = (c % kChunksPerRow) * 8;
       const int row = (prow / 32) * Cfg::WM + i * 32 + (prow % 32);
       if (row >= rows_left || col >= cols_left) continue;
