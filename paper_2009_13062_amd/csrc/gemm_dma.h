@@ -1,0 +1,161 @@
+// bf16 MFMA contraction with a multi-stage, direct-to-LDS pipeline (gfx950): the kernel used when
+// a problem is made of whole tiles (rows % BM == 0, cols % BN == 0, K % BK == 0, 16-byte aligned
+// rows).  Same contract as gemm_mfma.h:  C[z][i][j] = sum_k A[z][i][k] * B[z][k][j] + epilogue,
+// z = independent input-weight pairs folded into the grid.
+//
+// Global loads write straight into LDS (global_load_lds_dwordx4: each wavefront instruction moves
+// 64 x 16 contiguous LDS bytes, every lane from its own global address), so no VGPR is spent on
+// staging and NS-1 k-steps can be in flight per workgroup.  Because the LDS side of such a load is
+// fixed (lane l -> byte 16 l of the 1 KB block), bank conflicts are avoided by permuting WHICH global
+// 16-byte chunk a lane fetches (an XOR swizzle), not where it lands:
+//   A tile [BM][BK] (k contiguous): chunk c of row r is stored at position c ^ s(r), s(r) = r % 8 for
+//     128-byte rows, (r / 2) % 4 for 64-byte rows, so the 8 rows hit by 8 neighbouring lanes of a
+//     16-byte fragment read fall into 8 distinct 16-byte bank groups.
+//   B tile [BK][BN] (column contiguous): chunk c of row k is stored at position c ^ 2 (k % 4), so the
+//     4 rows x 32 bytes touched by one 16-lane group of a transposing read (ds_read_b64_tr_b16)
+//     fall into distinct bank groups.
+// Waiting is explicit: a thread's loads retire in order, so "stage kt has landed" is
+// s_waitcnt vmcnt(loads issued after it); a workgroup barrier then publishes every thread's share
+// and, at the same time, proves that the stage read in the previous step is free to be refilled.
+#pragma once
+#include "gemm_mfma.h"
+
+namespace nf {
+
+typedef __attribute__((address_space(3))) unsigned char lds_u8_t;
+typedef __attribute__((address_space(1))) const unsigned char glb_u8_t;
+
+template <int BM, int BN, int BK, int WGM, int WGN, int NS>
+struct DmaCfg {
+  static_assert(BK == 32 || BK == 64, "k-step of 32 or 64");
+  static constexpr int kBM = BM, kBN = BN, kBK = BK, kWGM = WGM, kWGN = WGN, kNS = NS;
+  static constexpr int kNW = WGM * WGN, kThreads = kNW * kWave;
+  static constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
+  static constexpr int kARow = BK * 2, kBRow = BN * 2;                 // bytes per LDS row
+  static constexpr int kABytes = BM * kARow, kBBytes = BK * kBRow, kStageBytes = kABytes + kBBytes;
+  static constexpr int kAInstr = kABytes / 1024 / kNW, kBInstr = kBBytes / 1024 / kNW;
+  static_assert(kAInstr * 1024 * kNW == kABytes && kBInstr * 1024 * kNW == kBBytes, "tile must split evenly");
+  static constexpr int kLoadsPerStage = kAInstr + kBInstr;
+  static constexpr int kInFlight = (NS - 2) * kLoadsPerStage;          // loads allowed to stay pending
+  static_assert(kInFlight < 64, "vmcnt has 6 bits");
+  static constexpr int kEpiPitch = BN + 4;
+  static constexpr int kLdsEpi = WGM * 32 * kEpiPitch * (int)sizeof(float);
+  static constexpr int kLdsPipe = NS * kStageBytes;
+  static constexpr int kLdsBytes = kLdsPipe > kLdsEpi ? kLdsPipe : kLdsEpi;
+  static constexpr int kACpr = BK / 8, kARpi = 64 / kACpr;              // A: chunks per row, rows per instruction
+  static constexpr int kBCpr = BN / 8, kBRpi = 64 / kBCpr;              // B: likewise
+  static_assert(kBRpi >= 1, "BN <= 512");
+  __device__ static __forceinline__ int swz_a(int row) { return (row * kACpr / 8) % kACpr; }
+};
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their "don't wait" maxima).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+template <class Cfg>
+__device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long lda, const bf16_t* __restrict__ B,
+                                              long ldb, int K, lds_u8_t* smem, bf16_t* C, const bf16_t* R,
+                                              long ldc, const Epilogue& ep, long row_vec_off, long col_vec_off) {
+  constexpr int FM = Cfg::FM, FN = Cfg::FN, NS = Cfg::kNS, BK = Cfg::kBK;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
+  const int half = lane / 32, l32 = lane % 32, l16 = lane % 16;
+
+  // ---- what this lane fetches: element offsets of its 16-byte chunks at k-step 0
+  long a_src[Cfg::kAInstr], b_src[Cfg::kBInstr];
+#pragma unroll
+  for (int t = 0; t < Cfg::kAInstr; ++t) {
+    const int row = (t * Cfg::kNW + wave) * Cfg::kARpi + lane / Cfg::kACpr;
+    const int c = (lane % Cfg::kACpr) ^ Cfg::swz_a(row);
+    a_src[t] = (long)row * lda + c * 8;
+  }
+#pragma unroll
+  for (int t = 0; t < Cfg::kBInstr; ++t) {
+    const int krow = (t * Cfg::kNW + wave) * Cfg::kBRpi + lane / Cfg::kBCpr;
+    const int c = (lane % Cfg::kBCpr) ^ (2 * (krow % 4));
+    b_src[t] = (long)krow * ldb + c * 8;
+  }
+  auto issue_stage = [&](int kt) {
+    lds_u8_t* stage = smem + (kt % NS) * Cfg::kStageBytes;
+    const bf16_t* a = A + (long)kt * BK;
+    const bf16_t* b = B + (long)kt * BK * ldb;
+#pragma unroll
+    for (int t = 0; t < Cfg::kAInstr; ++t)
+      __builtin_amdgcn_global_load_lds((glb_u8_t*)(a + a_src[t]), stage + (t * Cfg::kNW + wave) * 1024, 16, 0, 0);
+#pragma unroll
+    for (int t = 0; t < Cfg::kBInstr; ++t)
+      __builtin_amdgcn_global_load_lds((glb_u8_t*)(b + b_src[t]), stage + Cfg::kABytes + (t * Cfg::kNW + wave) * 1024,
+                                       16, 0, 0);
+  };
+
+  // ---- where this lane reads its fragments (byte offsets inside a stage, k-step part added later)
+  int a_off[FM], b_off[FN][2];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) a_off[i] = (wm * Cfg::WM + i * 32 + l32) * Cfg::kARow;
+  const int a_swz = Cfg::swz_a(l32);                  // row offsets above are multiples of 8: same swizzle
+#pragma unroll
+  for (int j = 0; j < FN; ++j)
+#pragma unroll
+    for (int hl = 0; hl < 2; ++hl) {
+      const int kr = 8 * half + l16 / 4 + 4 * hl;     // row inside a 16-k step; kr % 4 = l16 / 4
+      const int n = wn * Cfg::WN + j * 32 + ((lane / 16) % 2) * 16 + (l16 % 4) * 4;
+      b_off[j][hl] = Cfg::kABytes + kr * Cfg::kBRow + (((n / 8) ^ (2 * (l16 / 4))) * 16) + ((n / 4) % 2) * 8;
+    }
+
+  f32x16_t acc[FM][FN];
+#pragma unroll
+  for (int i = 0; i < FM; ++i)
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = K / BK;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nk) issue_stage(s);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    // stage kt has landed once at most the loads of the NS-2 younger stages are pending; near the
+    // end fewer stages were issued, so wait for everything.
+    if (kt + NS - 2 < nk) wait_vmcnt<Cfg::kInFlight>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    if (kt + NS - 1 < nk) issue_stage(kt + NS - 1);   // refills the stage read in step kt-1
+    const lds_u8_t* stage = smem + (kt % NS) * Cfg::kStageBytes;
+    // fragments are double buffered: those of 16-k step kk+1 are requested before the MFMAs of
+    // step kk issue, so LDS latency hides behind the matrix pipe
+    bf16x8_t af[2][FM], bfr[2][FN];
+    auto load_frags = [&](int kk, bf16x8_t (&a)[FM], bf16x8_t (&b)[FN]) {
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+        a[i] = *(const lds_bf16x8_t*)(stage + a_off[i] + (((2 * kk + half) ^ a_swz) * 16));
+#pragma unroll
+      for (int j = 0; j < FN; ++j) {
+        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][0] + kk * 16 * Cfg::kBRow));
+        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][1] + kk * 16 * Cfg::kBRow));
+        const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        b[j] = __builtin_bit_cast(bf16x8_t, both);
+      }
+    };
+    load_frags(0, af[0], bfr[0]);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      if (kk + 1 < BK / 16) load_frags(kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
+      __builtin_amdgcn_sched_barrier(0);     // keep the next step's LDS reads ahead of this step's MFMAs
+#pragma unroll
+      for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  __syncthreads();   // every wave is done with the last stage before the epilogue reuses LDS
+  gemm_epilogue<Cfg>(acc, (lds_f32_t*)smem, C, R, ldc, Cfg::kBM, Cfg::kBN, ep, row_vec_off, col_vec_off);
+}
+
+}  // namespace nf

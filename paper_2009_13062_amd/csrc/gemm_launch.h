@@ -27,6 +27,15 @@ enum TileId { T128x128 = 0, T128x256, T256x128, T64x128, T64x64, T32x128, T256x2
 constexpr int kTileBM[kNumTiles] = {128, 128, 256, 64, 64, 32, 256, 128, 128};
 constexpr int kTileBN[kNumTiles] = {128, 256, 128, 128, 64, 128, 256, 256, 128};
 
+// Direct-to-LDS pipelined kernels for problems made of whole tiles (BM x BN, k-step, stages).
+enum DmaTileId { D256x256k32s4 = 0, D128x256k32s5, D128x128k64s3, D128x128k32s4, D256x128k32s4, D128x128k32s8,
+                 D128x256k64s3, kNumDmaTiles };
+constexpr int kDmaBM[kNumDmaTiles] = {256, 128, 128, 128, 256, 128, 128};
+constexpr int kDmaBN[kNumDmaTiles] = {256, 256, 128, 128, 128, 128, 256};
+constexpr int kDmaBK[kNumDmaTiles] = {32, 32, 64, 32, 32, 32, 64};
+// dense, 16-byte aligned A and B; NF_EUNSUPPORTED if the problem is not a whole number of tiles
+nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s);
+
 // BKIND: 8 / 4 / 1 = dense B read with that vector width; 0 = implicit (im2col) B.
 // align_a: 16, 8, 4 or 2 = byte alignment of every A row start (and K a multiple of align_a/2).
 template <int BKIND>

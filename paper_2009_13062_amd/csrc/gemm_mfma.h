@@ -242,6 +242,94 @@ struct TileCfg {
   static constexpr int kLdsBytes = kLdsPipe > kLdsEpi ? kLdsPipe : kLdsEpi;
 };
 
+// ------------------------------------------------------------------------------------------
+// Epilogue shared by the contraction kernels.  acc[i][j] holds rows wm*WM + 32 i .. and columns
+// wn*WN + 32 j .. of the tile, transposed: register r of lane l is row (l % 32), column
+// 8 (r/4) + 4 (l/32) + r % 4 of the 32x32 block.  One 32-row block of every wave row per pass goes
+// through LDS (Es, fp32) so that rows leave the workgroup 16 bytes per lane.  All threads of the
+// workgroup must call it, after a barrier that ends every other use of the LDS behind Es.
+// ------------------------------------------------------------------------------------------
+template <class Cfg>
+__device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[Cfg::FM][Cfg::FN], lds_f32_t* const Es, bf16_t* C,
+                                              const bf16_t* R, long ldc, int rows_left, int cols_left,
+                                              const Epilogue& ep, long row_vec_off, long col_vec_off) {
+  constexpr int FM = Cfg::FM, FN = Cfg::FN;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
+  const int half = lane / 32, l32 = lane % 32;
+  // ---- epilogue, one 32-row block of each wave row per pass
+  constexpr int kEP = Cfg::kEpiPitch;
+  constexpr int kChunksPerRow = Cfg::kBN / 8;
+  constexpr int kPassChunks = Cfg::kWGM * 32 * kChunksPerRow;
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    {
+      const int row = wm * Cfg::WM + i * 32 + l32;           // this lane's row in the tile
+      float rb = 0.f, rs = 1.f, rt = 0.f;
+      if (row < rows_left) {
+        if (ep.row_bias) rb = ep.row_bias[row_vec_off + row];
+        if (ep.row_scale) { rs = ep.row_scale[row_vec_off + row]; rt = ep.row_shift[row_vec_off + row]; }
+      }
+      lds_f32_t* erow = Es + (wm * 32 + l32) * kEP + wn * Cfg::WN + half * 4;
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int col = wn * Cfg::WN + j * 32 + q * 8 + half * 4;
+          f32x4v_t v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float t = acc[i][j][q * 4 + e];
+            if (ep.col_bias) t += (col + e < cols_left) ? ep.col_bias[col_vec_off + col + e] : 0.f;
+            t = fmaf(t + rb, rs, rt);
+            if (ep.act_before_residual) t = apply_act(t, ep.act);
+            v[e] = t;
+          }
+          *(lds_f32x4_t*)(erow + j * 32 + q * 8) = v;
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < kPassChunks; c += Cfg::kThreads) {
+      const int prow = c / kChunksPerRow, col = (c % kChunksPerRow) * 8;
+      const int row = (prow / 32) * Cfg::WM + i * 32 + (prow % 32);
+      if (row >= rows_left || col >= cols_left) continue;
+      const lds_f32_t* src = Es + prow * kEP + col;
+      const f32x4v_t v0 = *(const lds_f32x4_t*)src, v1 = *(const lds_f32x4_t*)(src + 4);
+      float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
+      const long o = (long)row * ldc + col;
+      if (ep.vec_store) {
+        if (R) {
+          const uint4 rr = *reinterpret_cast<const uint4*>(R + o);
+          const uint32_t w[4] = {rr.x, rr.y, rr.z, rr.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[2 * e] += __uint_as_float(w[e] << 16);
+            v[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
+          }
+        }
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float a0 = v[2 * e], a1 = v[2 * e + 1];
+          if (!ep.act_before_residual) { a0 = apply_act(a0, ep.act); a1 = apply_act(a1, ep.act); }
+          w[e] = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
+        }
+        *reinterpret_cast<uint4*>(C + o) = make_uint4(w[0], w[1], w[2], w[3]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (col + e >= cols_left) break;
+          float t = v[e];
+          if (R) t += bf16_to_f32(R[o + e]);
+          if (!ep.act_before_residual) t = apply_act(t, ep.act);
+          C[o + e] = f32_to_bf16(t);
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
 template <class Cfg, class ALoader, class BLoader>
 __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_bf16_t* smem,
                                           bf16_t* C, const bf16_t* R, long ldc, int rows_left,
@@ -319,78 +407,7 @@ __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_b
     __syncthreads();
   }
 
-  // ---- epilogue, one 32-row block of each wave row per pass
-  lds_f32_t* const Es = (lds_f32_t*)smem;
-  constexpr int kEP = Cfg::kEpiPitch;
-  constexpr int kChunksPerRow = Cfg::kBN / 8;
-  constexpr int kPassChunks = Cfg::kWGM * 32 * kChunksPerRow;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-    {
-      const int row = wm * Cfg::WM + i * 32 + l32;           // this lane's row in the tile
-      float rb = 0.f, rs = 1.f, rt = 0.f;
-      if (row < rows_left) {
-        if (ep.row_bias) rb = ep.row_bias[row_vec_off + row];
-        if (ep.row_scale) { rs = ep.row_scale[row_vec_off + row]; rt = ep.row_shift[row_vec_off + row]; }
-      }
-      lds_f32_t* erow = Es + (wm * 32 + l32) * kEP + wn * Cfg::WN + half * 4;
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int col = wn * Cfg::WN + j * 32 + q * 8 + half * 4;
-          f32x4v_t v;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float t = acc[i][j][q * 4 + e];
-            if (ep.col_bias) t += (col + e < cols_left) ? ep.col_bias[col_vec_off + col + e] : 0.f;
-            t = fmaf(t + rb, rs, rt);
-            if (ep.act_before_residual) t = apply_act(t, ep.act);
-            v[e] = t;
-          }
-          *(lds_f32x4_t*)(erow + j * 32 + q * 8) = v;
-        }
-    }
-    __syncthreads();
-    for (int c = tid; c < kPassChunks; c += Cfg::kThreads) {
-      const int prow = c / kChunksPerRow, col = (c % kChunksPerRow) * 8;
-      const int row = (prow / 32) * Cfg::WM + i * 32 + (prow % 32);
-      if (row >= rows_left || col >= cols_left) continue;
-      const lds_f32_t* src = Es + prow * kEP + col;
-      const f32x4v_t v0 = *(const lds_f32x4_t*)src, v1 = *(const lds_f32x4_t*)(src + 4);
-      float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-      const long o = (long)row * ldc + col;
-      if (ep.vec_store) {
-        if (R) {
-          const uint4 rr = *reinterpret_cast<const uint4*>(R + o);
-          const uint32_t w[4] = {rr.x, rr.y, rr.z, rr.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            v[2 * e] += __uint_as_float(w[e] << 16);
-            v[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
-          }
-        }
-        uint32_t w[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float a0 = v[2 * e], a1 = v[2 * e + 1];
-          if (!ep.act_before_residual) { a0 = apply_act(a0, ep.act); a1 = apply_act(a1, ep.act); }
-          w[e] = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
-        }
-        *reinterpret_cast<uint4*>(C + o) = make_uint4(w[0], w[1], w[2], w[3]);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          if (col + e >= cols_left) break;
-          float t = v[e];
-          if (R) t += bf16_to_f32(R[o + e]);
-          if (!ep.act_before_residual) t = apply_act(t, ep.act);
-          C[o + e] = f32_to_bf16(t);
-        }
-      }
-    }
-    __syncthreads();
-  }
+  gemm_epilogue<Cfg>(acc, (lds_f32_t*)smem, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off);
 }
 
 }  // namespace nf

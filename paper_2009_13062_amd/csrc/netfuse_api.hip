@@ -65,6 +65,31 @@ int forced_tile() {
   return v;
 }
 
+// Optional override for sweeps of the direct-to-LDS kernels: NETFUSE_DMA=<index into DmaTileId>, or -1
+// to disable them.
+int forced_dma() {
+  static const int v = [] {
+    const char* e = getenv("NETFUSE_DMA");
+    if (!e || !*e) return -2;
+    const int t = atoi(e);
+    return (t >= -1 && t < kNumDmaTiles) ? t : -2;
+  }();
+  return v;
+}
+
+// Direct-to-LDS kernel for a dense, fully aligned problem made of whole tiles, or -1.
+int pick_dma(int rows, int cols, int K, long long problems) {
+  const int f = forced_dma();
+  if (f == -1) return -1;
+  auto fits = [&](int t) { return rows % kDmaBM[t] == 0 && cols % kDmaBN[t] == 0 && K % kDmaBK[t] == 0; };
+  if (f >= 0) return fits(f) ? f : -1;
+  // measured on MI355X: 256x256 tiles win once there are >= 4 workgroups per CU, otherwise 128x128
+  // tiles with a 32-deep k-step, 8 waves and 4 stages (two workgroups per CU)
+  if (fits(D256x256k32s4) && problems * (rows / 256) * (cols / 256) >= 1024) return D256x256k32s4;
+  if (fits(D128x128k32s4)) return D128x128k32s4;
+  return -1;
+}
+
 // Tile choice.  Measured on MI355X: with one k-step of prefetch the kernel is bound by load latency,
 // and 8 wavefronts on a 128x128 tile (3 workgroups per CU) hide it best; small problems take the
 // smallest tile that covers them.
@@ -138,6 +163,10 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     a.ep.col_bias = bias; a.ep.col_vec_stride0 = Nout;
     a.ep.act = act; a.ep.act_before_residual = 1;
     a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16);
+    if (bkind == 8 && al == 16) {
+      const int d = pick_dma(N, Nout, K, M);
+      if (d >= 0) return launch_gemm_dma(d, L, s);
+    }
     return launch_gemm_any(bkind, al, pick_tile(N, Nout, M), L, s);
   }
   const int tiles_m = (N + 63) / 64, tiles_n = (Nout + 63) / 64;
