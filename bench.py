@@ -202,7 +202,31 @@ def make_graph(torch, fn):
     return g.replay
 
 
-def run_workload(name, steps, warmup, use_graph, torch, nf, sep_steps=None):
+def load_traffic(name):
+    """HBM bytes per launch of the dominant kernel, measured offline with rocprofv3 --pmc (FETCH_SIZE,
+    WRITE_SIZE, calibrated against --calibrate-copy) and recorded under profiles/; None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        return json.load(f).get(name)
+
+
+def calibrate_copy(torch, nf):
+    """A plain copy of known size (netfuse_merge_transpose with M = 1 is src -> dst), for scaling the
+    FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run."""
+    rows, H = 65536, 2048                                   # 256 MiB of bf16 in, 256 MiB out
+    src = torch.empty((1, rows, H), dtype=torch.bfloat16, device="cuda").normal_()
+    dst = torch.empty((rows, H), dtype=torch.bfloat16, device="cuda")
+    for _ in range(5):
+        nf.merge_transpose(src, 1, True, out=dst)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibrate_copy": {"kernel": "merge_transpose_kernel", "launches": 5,
+                                         "bytes_read_per_launch": src.numel() * 2,
+                                         "bytes_written_per_launch": dst.numel() * 2}}))
+
+
+def run_workload(name, steps, warmup, use_graph, torch, nf, sep_steps=None, separate_too=True):
     net, x, singles, cfg, M = build_workload(name, torch)
     merged = lambda: net.forward(x)
 
@@ -224,21 +248,24 @@ def run_workload(name, steps, warmup, use_graph, torch, nf, sep_steps=None):
             res["graph_error"] = repr(ex)[:200]
     res["ms_per_step"] = best
     res["inferences_per_s"] = M / (best * 1e-3)
-    ss = sep_steps or max(2, steps // 4)
-    sw, se = timed(torch, separate, ss, max(1, warmup // 2))
-    sep_best = sw
-    res["separate_eager_ms"] = sw
-    if use_graph:
-        try:
-            replay_s = make_graph(torch, separate)
-            sgw, _ = timed(torch, replay_s, ss, max(1, warmup // 2))
-            res["separate_graph_ms"] = sgw
-            sep_best = min(sep_best, sgw)
-        except Exception as ex:
-            res["separate_graph_error"] = repr(ex)[:200]
-    res["separate_ms"] = sep_best
-    res["separate_inferences_per_s"] = M / (sep_best * 1e-3)
-    res["speedup_vs_separate"] = sep_best / best
+    if separate_too:
+        ss = sep_steps or max(2, steps // 4)
+        sw, se = timed(torch, separate, ss, max(1, warmup // 2))
+        sep_best = sw
+        res["separate_eager_ms"] = sw
+        if use_graph:
+            try:
+                replay_s = make_graph(torch, separate)
+                sgw, _ = timed(torch, replay_s, ss, max(1, warmup // 2))
+                res["separate_graph_ms"] = sgw
+                sep_best = min(sep_best, sgw)
+            except Exception as ex:
+                res["separate_graph_error"] = repr(ex)[:200]
+        res["separate_ms"] = sep_best
+        res["separate_inferences_per_s"] = M / (sep_best * 1e-3)
+        res["speedup_vs_separate"] = sep_best / best
+    else:
+        res["separate_ms"] = res["separate_inferences_per_s"] = res["speedup_vs_separate"] = None
     # per-kernel pass: the same steps, un-graphed, HIP events around every launch
     with OpTimer(nf, torch) as ot:
         for _ in range(max(3, min(steps, 10))):
@@ -248,6 +275,7 @@ def run_workload(name, steps, warmup, use_graph, torch, nf, sep_steps=None):
                               GBps=v["bytes"] / (v["ms"] * 1e-3) / 1e9, TFLOPs=v["flops"] / (v["ms"] * 1e-3) / 1e12)
                       for k, v in sorted(agg.items(), key=lambda kv: -kv[1]["ms"])}
     res["roofline"] = roofline_for(agg)
+    res["roofline"]["traffic"] = load_traffic(name)
     total_fl = sum(v["flops"] for v in agg.values()) / max(3, min(steps, 10))
     res["model_TFLOPs"] = total_fl / (best * 1e-3) / 1e12
     return res
@@ -295,6 +323,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quick", action="store_true", help="headline workload only, no CPU baseline")
+    ap.add_argument("--no-separate", action="store_true", help="skip the M-separate-launches leg (profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true", help="only run a plain copy of known size and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (models are independent: sharding M over GPUs needs no "
@@ -305,10 +335,15 @@ def main():
     import paper_2009_13062_amd as nf
     torch.cuda.set_device(0)
 
+    if args.calibrate_copy:
+        calibrate_copy(torch, nf)
+        return
     t_start = time.time()
-    head = run_workload(args.workload, args.steps, args.warmup, not args.no_graph, torch, nf)
-    log("[bench] %s: %.3f ms/step, %.1f inf/s, %.2fx vs separate (%.1f s)" % (
-        args.workload, head["ms_per_step"], head["inferences_per_s"], head["speedup_vs_separate"], time.time() - t_start))
+    head = run_workload(args.workload, args.steps, args.warmup, not args.no_graph, torch, nf,
+                        separate_too=not args.no_separate)
+    log("[bench] %s: %.3f ms/step, %.1f inf/s, %sx vs separate (%.1f s)" % (
+        args.workload, head["ms_per_step"], head["inferences_per_s"],
+        "%.2f" % head["speedup_vs_separate"] if head["speedup_vs_separate"] else "-", time.time() - t_start))
     others = {}
     if not args.quick and args.others:
         for name in [n for n in args.others.split(",") if n and n != args.workload]:
