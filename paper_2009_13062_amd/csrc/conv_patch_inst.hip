@@ -1,0 +1,46 @@
+// Instantiation and launch of the patch-gather convolution kernels (3x3, bf16).
+#include <atomic>
+
+#include "conv_patch.h"
+#include "gemm_launch.h"
+
+namespace nf {
+
+template <class Cfg>
+static nf_status launch_one(ConvPatchArgs& a, int B, hipStream_t s) {
+  a.tiles_m = (a.cog + Cfg::kBM - 1) / Cfg::kBM;
+  a.tiles_n = (a.HoWo + Cfg::kBN - 1) / Cfg::kBN;
+  const long long total = (long long)a.tiles_m * a.tiles_n * a.nG * B;
+  if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
+  a.PS = (a.PS + 7) / 8 * 8;                       // planes keep the 16-byte alignment of their rows
+  if ((long long)Cfg::kCB * (a.PS / a.PW) * a.cpr > Cfg::kPatchTasksMax) return NF_EUNSUPPORTED;
+  const int lds = Cfg::lds_bytes(a.PS);
+  if (lds > 160 * 1024) return NF_EUNSUPPORTED;
+  auto kern = conv_patch_kernel<Cfg>;
+  if (lds > 64 * 1024) {
+    static std::atomic<int> opted_in{0};
+    if (opted_in.load(std::memory_order_acquire) < lds) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              160 * 1024) != hipSuccess)
+        return NF_ELAUNCH;
+      opted_in.store(160 * 1024, std::memory_order_release);
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(256), lds, s, a);
+  return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
+}
+
+// 3x3, dilation 1, cig % 16 == 0, patch width <= 64.  The caller has filled everything but the tiling.
+nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
+  // the tallest row tile that still gives every CU two workgroups
+  const long long per_row_tile = (long long)((a.HoWo + 127) / 128) * a.nG * B;
+  auto tiles = [&](int bm) { return per_row_tile * ((a.cog + bm - 1) / bm); };
+  // 32 channels per stage (half as many barriers) where the patch copy still fits 8 chunks per thread
+  const bool deep = a.cig % 32 == 0 && a.cig >= 128 && 32LL * ((a.PS + a.PW - 1) / a.PW) * a.cpr <= 8 * 256;
+  if (a.cog > 64 && tiles(128) >= 512) return launch_one<ConvPatchCfg<128, 3, 3, 16, 2, 2>>(a, B, s);
+  if (a.cog > 32 && tiles(64) >= 512)
+    return deep ? launch_one<ConvPatchCfg<64, 3, 3, 32, 1, 4>>(a, B, s) : launch_one<ConvPatchCfg<64, 3, 3, 16, 1, 4>>(a, B, s);
+  return deep ? launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4>>(a, B, s) : launch_one<ConvPatchCfg<32, 3, 3, 16, 1, 4>>(a, B, s);
+}
+
+}  // namespace nf

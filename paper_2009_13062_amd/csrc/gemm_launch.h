@@ -41,4 +41,8 @@ nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s);
 template <int BKIND>
 nf_status launch_gemm_bkind(int align_a, int tile, GemmLaunch& L, hipStream_t s);
 
+struct ConvPatchArgs;
+// 3x3 convolution through the LDS patch-gather kernel (conv_patch.h); see netfuse_conv2d for the conditions.
+nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s);
+
 }  // namespace nf

@@ -6,8 +6,11 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
+
 #include "../../include/netfuse.h"
 #include "attention_kernels.h"
+#include "conv_patch.h"
 #include "gemm_launch.h"
 #include "gemm_mfma.h"
 #include "generic_kernels.h"
@@ -239,6 +242,30 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
       if (al_b == 16 && HoWo % 8 == 0) bkind = 8;
       else if (al_b >= 8 && HoWo % 4 == 0) bkind = 4;
       return launch_gemm_any(bkind, al, tile, L, s);
+    }
+    static const bool no_patch = getenv("NETFUSE_NO_PATCH") != nullptr;
+    // patch geometry (conv_patch.h): image column ix sits at patch column ix + 8; rows are copied in
+    // chunks of VW pixels; a 128-position tile touches at most `span` output rows
+    const int VW = W % 8 == 0 ? 8 : (W % 4 == 0 ? 4 : (W % 2 == 0 ? 2 : 1));
+    const int maxcol = std::max(kLPad + W - 1, ((int)Wo - 1) * stride + KW - 1 - pad + kLPad);
+    const int PWp = (maxcol + 1 + 7) / 8 * 8;
+    const int span = (int)std::min<long long>(Ho, (126 + Wo) / Wo + 1);
+    const int PHmax = (span - 1) * stride + KH;
+    const long long patch_tasks = 16LL * PHmax * (W / VW);          // chunk copies per 16-channel block
+    if (!no_patch && KH == 3 && KW == 3 && dilation == 1 && cig % 16 == 0 && pad <= kLPad && patch_tasks <= 8 * 256 &&
+        aligned(w, 16) && aligned(x, 16)) {
+      // k x k: gather MFMA operands from an LDS copy of the zero-padded input patch (conv_patch.h)
+      ConvPatchArgs c;
+      memset(&c, 0, sizeof(c));
+      c.x = (const bf16_t*)x; c.w = (const bf16_t*)w; c.R = (const bf16_t*)residual; c.y = (bf16_t*)y;
+      c.cig = cig; c.cog = cog; c.nG = M * g; c.H = H; c.W = W; c.Ho = (int)Ho; c.Wo = (int)Wo; c.HoWo = HoWo;
+      c.stride = stride; c.pad = pad;
+      c.PW = PWp; c.VW = VW; c.cpr = W / VW;
+      c.PS = PHmax * PWp;               // padded per kernel configuration at launch
+      c.x_group = (long)cig * H * W; c.x_image = (long)Ctot_in * H * W;
+      c.y_group = (long)cog * HoWo; c.y_image = (long)Ctot_out * HoWo;
+      c.ep = a.ep;
+      return launch_conv_patch_3x3(c, B, s);
     }
     a.geom.H = H; a.geom.W = W; a.geom.KH = KH; a.geom.KW = KW; a.geom.Wo = (int)Wo;
     a.geom.stride = stride; a.geom.pad = pad; a.geom.dil = dilation;

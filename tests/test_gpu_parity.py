@@ -144,6 +144,11 @@ CONV_CASES = [
     (2, 2, 32, 64, 4, 9, 11, 3, 3, 1, 1, 1),       # batch 2 per model, non-square image
     (1, 1, 16, 24, 1, 10, 10, 3, 3, 1, 2, 2),      # dilation 2
     (3, 1, 8, 200, 2, 5, 5, 2, 3, 1, 1, 1),        # non-square kernel, 100 outputs per group
+    (2, 1, 128, 256, 1, 28, 28, 3, 3, 1, 1, 1),    # patch-gather 3x3: two 128-channel row tiles, 7 position tiles
+    (3, 2, 32, 32, 2, 7, 7, 3, 3, 1, 1, 1),        # patch-gather, 16 channels per group, image smaller than a tile
+    (1, 1, 64, 64, 1, 56, 56, 3, 3, 1, 1, 1),      # patch-gather, 58-wide patch, tiles that start mid-row
+    (2, 1, 64, 128, 1, 30, 30, 3, 3, 2, 1, 1),     # patch-gather, stride 2, odd output width 15
+    (2, 1, 48, 64, 1, 12, 12, 3, 3, 1, 0, 1),      # patch-gather, no padding, 3 channel blocks
 ]
 
 
