@@ -52,7 +52,7 @@ struct ConvPatchCfg {
   static constexpr int kABytes = BM * kAPitch * 2;
   static constexpr int kEpiPitch = kBN + 4;
   static constexpr int kLdsEpi = WGM * 32 * kEpiPitch * (int)sizeof(float);
-  static constexpr int kPatchTasksMax = 8 * 256;
+  static constexpr int kPatchTasksMax = 12 * 256;
   static constexpr int lds_bytes(int PS) {
     const int pipe = kABytes + (CB * PS + kHalfShift) * 2;
     return pipe > kLdsEpi ? pipe : kLdsEpi;
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
   // one (channel, patch row)); the task geometry does not change from block to block
   constexpr int kCpr = Cfg::kStageK / 8;
   constexpr int kAChunks = Cfg::kBM * kCpr, kAPer = (kAChunks + 255) / 256;
-  constexpr int kNT = 8;                                   // patch tasks per thread (the host checks the bound)
+  constexpr int kNT = Cfg::kPatchTasksMax / 256;            // patch tasks per thread (the host checks the bound)
   int g_off[kNT], l_off[kNT];                              // element offsets; g_off < 0: nothing to copy
   {
     const int ntasks = CB * PH * a.cpr;

@@ -36,7 +36,7 @@ nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
   const long long per_row_tile = (long long)((a.HoWo + 127) / 128) * a.nG * B;
   auto tiles = [&](int bm) { return per_row_tile * ((a.cog + bm - 1) / bm); };
   // 32 channels per stage (half as many barriers) where the patch copy still fits 8 chunks per thread
-  const bool deep = a.cig % 32 == 0 && a.cig >= 128 && 32LL * ((a.PS + a.PW - 1) / a.PW) * a.cpr <= 8 * 256;
+  const bool deep = a.cig % 32 == 0 && a.cig >= 128 && 32LL * ((a.PS + a.PW - 1) / a.PW) * a.cpr <= 12 * 256;
   if (a.cog > 64 && tiles(128) >= 512) return launch_one<ConvPatchCfg<128, 3, 3, 16, 2, 2>>(a, B, s);
   if (a.cog > 32 && tiles(64) >= 512)
     return deep ? launch_one<ConvPatchCfg<64, 3, 3, 32, 1, 4>>(a, B, s) : launch_one<ConvPatchCfg<64, 3, 3, 16, 1, 4>>(a, B, s);

@@ -252,7 +252,7 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     const int span = (int)std::min<long long>(Ho, (126 + Wo) / Wo + 1);
     const int PHmax = (span - 1) * stride + KH;
     const long long patch_tasks = 16LL * PHmax * (W / VW);          // chunk copies per 16-channel block
-    if (!no_patch && KH == 3 && KW == 3 && dilation == 1 && cig % 16 == 0 && pad <= kLPad && patch_tasks <= 8 * 256 &&
+    if (!no_patch && KH == 3 && KW == 3 && dilation == 1 && cig % 16 == 0 && pad <= kLPad && patch_tasks <= 12 * 256 &&
         aligned(w, 16) && aligned(x, 16)) {
       // k x k: gather MFMA operands from an LDS copy of the zero-padded input patch (conv_patch.h)
       ConvPatchArgs c;
