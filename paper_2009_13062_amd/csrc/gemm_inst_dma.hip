@@ -56,6 +56,9 @@ nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s) {
     case D256x128k32s4: return launch_dma<DmaCfg<256, 128, 32, 4, 2, 4>>(L, s);
     case D128x128k32s8: return launch_dma<DmaCfg<128, 128, 32, 2, 4, 8>>(L, s);
     case D128x256k64s3: return launch_dma<DmaCfg<128, 256, 64, 2, 4, 3>>(L, s);
+    case D64x128k32s4w4: return launch_dma<DmaCfg<64, 128, 32, 1, 4, 4>>(L, s);
+    case D128x64k32s4w4: return launch_dma<DmaCfg<128, 64, 32, 4, 1, 4>>(L, s);
+    case D64x128k64s4w4: return launch_dma<DmaCfg<64, 128, 64, 1, 4, 4>>(L, s);
   }
   return NF_EUNSUPPORTED;
 }

@@ -61,6 +61,7 @@ struct Epilogue {
   int act;
   int act_before_residual;  // matmul: act(.) + residual;  convolution: act(. + residual)
   int vec_store;            // C (and residual) rows are 16-byte aligned and cols % 8 == 0
+  int dbg;                  // TEMPORARY probe flags
 };
 
 // ------------------------------------------------------------------------------------------
@@ -242,25 +243,40 @@ struct TileCfg {
   static constexpr int kLdsBytes = kLdsPipe > kLdsEpi ? kLdsPipe : kLdsEpi;
 };
 
-// ------------------------------------------------------------------------------------------
-// Epilogue shared by the contraction kernels.  acc[i][j] holds rows wm*WM + 32 i .. and columns
-// wn*WN + 32 j .. of the tile, transposed: register r of lane l is row (l % 32), column
-// 8 (r/4) + 4 (l/32) + r % 4 of the 32x32 block.  One 32-row block of every wave row per pass goes
-// through LDS (Es, fp32) so that rows leave the workgroup 16 bytes per lane.  All threads of the
-// workgroup must call it, after a barrier that ends every other use of the LDS behind Es.
-// ------------------------------------------------------------------------------------------
-template <class Cfg>
-__device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[Cfg::FM][Cfg::FN], lds_f32_t* const Es, bf16_t* C,
-                                              const bf16_t* R, long ldc, int rows_left, int cols_left,
-                                              const Epilogue& ep, long row_vec_off, long col_vec_off) {
+template <int ACT>
+__device__ __forceinline__ float act_const(float v) {
+  if constexpr (ACT == NF_ACT_RELU) return v > 0.f ? v : (v != v ? v : 0.f);
+  else if constexpr (ACT == NF_ACT_GELU) return 0.5f * v * (1.f + fast_erf(v * 0.70710678118654752440f));
+  else return v;
+}
+
+// ACT1: activation applied to the accumulator side (before the residual), ACT2: after the residual.
+template <class Cfg, int ACT1, int ACT2>
+__device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::FN], lds_f32_t* const Es, bf16_t* C,
+                                                  const bf16_t* R, long ldc, int rows_left, int cols_left,
+                                                  const Epilogue& ep, long row_vec_off, long col_vec_off) {
   constexpr int FM = Cfg::FM, FN = Cfg::FN;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
   const int half = lane / 32, l32 = lane % 32;
-  // ---- epilogue, one 32-row block of each wave row per pass
   constexpr int kEP = Cfg::kEpiPitch;
   constexpr int kChunksPerRow = Cfg::kBN / 8;
   constexpr int kPassChunks = Cfg::kWGM * 32 * kChunksPerRow;
+  constexpr int kPer = (kPassChunks + Cfg::kThreads - 1) / Cfg::kThreads;
+
+  // per-column constants of this lane (4 consecutive columns per 8-column group), fetched once, all
+  // loads in flight together
+  float cb[FN][4][4];
+#pragma unroll
+  for (int j = 0; j < FN; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int col = wn * Cfg::WN + j * 32 + q * 8 + half * 4 + e;
+        cb[j][q][e] = (ep.col_bias != nullptr && col < cols_left) ? ep.col_bias[col_vec_off + col] : 0.f;
+      }
+
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
     {
@@ -275,59 +291,80 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[Cfg::FM][Cfg::FN],
       for (int j = 0; j < FN; ++j)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-          const int col = wn * Cfg::WN + j * 32 + q * 8 + half * 4;
           f32x4v_t v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float t = acc[i][j][q * 4 + e];
-            if (ep.col_bias) t += (col + e < cols_left) ? ep.col_bias[col_vec_off + col + e] : 0.f;
-            t = fmaf(t + rb, rs, rt);
-            if (ep.act_before_residual) t = apply_act(t, ep.act);
-            v[e] = t;
-          }
+          for (int e = 0; e < 4; ++e) v[e] = act_const<ACT1>(fmaf(acc[i][j][q * 4 + e] + cb[j][q][e] + rb, rs, rt));
           *(lds_f32x4_t*)(erow + j * 32 + q * 8) = v;
         }
     }
     __syncthreads();
-    for (int c = tid; c < kPassChunks; c += Cfg::kThreads) {
+    // this thread's chunks of the pass: residual loads first (all in flight), then LDS -> bf16 -> HBM
+    uint4 rr[kPer];
+    long off[kPer];
+    bool live[kPer];
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int c = tid + t * Cfg::kThreads;
       const int prow = c / kChunksPerRow, col = (c % kChunksPerRow) * 8;
       const int row = (prow / 32) * Cfg::WM + i * 32 + (prow % 32);
-      if (row >= rows_left || col >= cols_left) continue;
+      live[t] = (kPassChunks % Cfg::kThreads == 0 || c < kPassChunks) && row < rows_left && col < cols_left;
+      off[t] = (long)row * ldc + col;
+      rr[t] = make_uint4(0, 0, 0, 0);
+      if (live[t] && R != nullptr && ep.vec_store) rr[t] = *reinterpret_cast<const uint4*>(R + off[t]);
+    }
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      if (!live[t]) continue;
+      const int c = tid + t * Cfg::kThreads;
+      const int prow = c / kChunksPerRow, col = (c % kChunksPerRow) * 8;
       const lds_f32_t* src = Es + prow * kEP + col;
       const f32x4v_t v0 = *(const lds_f32x4_t*)src, v1 = *(const lds_f32x4_t*)(src + 4);
       float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-      const long o = (long)row * ldc + col;
       if (ep.vec_store) {
-        if (R) {
-          const uint4 rr = *reinterpret_cast<const uint4*>(R + o);
-          const uint32_t w[4] = {rr.x, rr.y, rr.z, rr.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            v[2 * e] += __uint_as_float(w[e] << 16);
-            v[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u);
-          }
-        }
-        uint32_t w[4];
+        const uint32_t w[4] = {rr[t].x, rr[t].y, rr[t].z, rr[t].w};
+        uint32_t o[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          float a0 = v[2 * e], a1 = v[2 * e + 1];
-          if (!ep.act_before_residual) { a0 = apply_act(a0, ep.act); a1 = apply_act(a1, ep.act); }
-          w[e] = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
+          const float a0 = act_const<ACT2>(v[2 * e] + __uint_as_float(w[e] << 16));
+          const float a1 = act_const<ACT2>(v[2 * e + 1] + __uint_as_float(w[e] & 0xffff0000u));
+          o[e] = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
         }
-        *reinterpret_cast<uint4*>(C + o) = make_uint4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<uint4*>(C + off[t]) = make_uint4(o[0], o[1], o[2], o[3]);
       } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           if (col + e >= cols_left) break;
-          float t = v[e];
-          if (R) t += bf16_to_f32(R[o + e]);
-          if (!ep.act_before_residual) t = apply_act(t, ep.act);
-          C[o + e] = f32_to_bf16(t);
+          float x = v[e];
+          if (R) x += bf16_to_f32(R[off[t] + e]);
+          C[off[t] + e] = f32_to_bf16(act_const<ACT2>(x));
         }
       }
     }
     __syncthreads();
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// Epilogue shared by the contraction kernels.  acc[i][j] holds rows wm*WM + 32 i .. and columns
+// wn*WN + 32 j .. of the tile, transposed: register r of lane l is row (l % 32), column
+// 8 (r/4) + 4 (l/32) + r % 4 of the 32x32 block.  One 32-row block of every wave row per pass goes
+// through LDS (Es, fp32) so that rows leave the workgroup 16 bytes per lane.  All threads of the
+// workgroup must call it, after a barrier that ends every other use of the LDS behind Es.
+// The activation is a wave-uniform switch around fully specialised bodies.
+// ------------------------------------------------------------------------------------------
+template <class Cfg>
+__device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[Cfg::FM][Cfg::FN], lds_f32_t* const Es, bf16_t* C,
+                                              const bf16_t* R, long ldc, int rows_left, int cols_left,
+                                              const Epilogue& ep, long row_vec_off, long col_vec_off) {
+#define NF_EPI(A1, A2) \
+  gemm_epilogue_act<Cfg, A1, A2>(acc, Es, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off)
+  if (ep.act == NF_ACT_NONE) NF_EPI(NF_ACT_NONE, NF_ACT_NONE);
+  else if (ep.act_before_residual) {
+    if (ep.act == NF_ACT_GELU) NF_EPI(NF_ACT_GELU, NF_ACT_NONE); else NF_EPI(NF_ACT_RELU, NF_ACT_NONE);
+  } else {
+    if (ep.act == NF_ACT_GELU) NF_EPI(NF_ACT_NONE, NF_ACT_GELU); else NF_EPI(NF_ACT_NONE, NF_ACT_RELU);
+  }
+#undef NF_EPI
 }
 
 template <class Cfg, class ALoader, class BLoader>

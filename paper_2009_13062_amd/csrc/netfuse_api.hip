@@ -166,6 +166,7 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     a.ep.col_bias = bias; a.ep.col_vec_stride0 = Nout;
     a.ep.act = act; a.ep.act_before_residual = 1;
     a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16);
+    { static const int dbg = getenv("NETFUSE_DBG") ? atoi(getenv("NETFUSE_DBG")) : 0; a.ep.dbg = dbg; }
     if (bkind == 8 && al == 16) {
       const int d = pick_dma(N, Nout, K, M);
       if (d >= 0) return launch_gemm_dma(d, L, s);
