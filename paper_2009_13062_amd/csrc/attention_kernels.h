@@ -83,37 +83,27 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a) {
 // bf16 MFMA kernel for head dimension 64.
 //
 // Workgroup = 4 wavefronts = 128 query rows of one (model, sequence, head); wave w owns 32 of them.
-// Keys are streamed through LDS 64 at a time.  Scores are computed TRANSPOSED, S^T = K Q^T, so the
-// 32x32 accumulator of a lane holds 16 keys of ONE query (lane % 32): the softmax statistics are
-// per-lane scalars (the two lane halves hold the same query and are merged with one cross-half
-// shuffle), and the exponentiated scores are already in the register order the second MFMA wants
-// for its B operand (O^T = V^T P^T), with the key order inside a 16-key step permuted identically
-// on the V^T side.  V is transposed 8x8 in registers on its way into LDS.
+// Keys and values are streamed through LDS 64 at a time, double buffered, with the next block's
+// global loads in flight in registers while the current one is used.  Scores are computed
+// TRANSPOSED, S^T = K Q^T, so the 32x32 accumulator of a lane holds 16 keys of ONE query
+// (lane % 32): the softmax statistics are per-lane scalars (the two lane halves hold the same query
+// and are merged with one cross-half shuffle), and the exponentiated scores are already in the
+// register order the second MFMA wants for its B operand (O^T = V^T P^T), with the key order inside
+// a 16-key step permuted identically on the V^T side.  V stays [key][feature] in LDS as in memory;
+// the V^T fragments come from the transposing LDS read (ds_read_b64_tr_b16).
 // ------------------------------------------------------------------------------------------
-// 8 (key) x 8 (feature) block held as 8 rows of 4 dwords -> 8 vectors of 8 consecutive keys.
-__device__ __forceinline__ void transpose_8x8_b16(const uint32_t (&in)[8][4], uint4 (&out)[8]) {
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    uint32_t w[4];
-#pragma unroll
-    for (int kp = 0; kp < 4; ++kp) {
-      const uint32_t lo = in[2 * kp][e / 2], hi = in[2 * kp + 1][e / 2];
-      w[kp] = (e & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
-    }
-    out[e] = make_uint4(w[0], w[1], w[2], w[3]);
-  }
-}
-
 constexpr int kAttnD = 64;
 constexpr int kAttnKB = 64;                 // keys per LDS stage
-constexpr int kAttnKPitch = kAttnD + 8;     // K tile  [key][t]
-constexpr int kAttnVPitch = kAttnKB + 4;    // V^T tile [t][key]; 136 B pitch, read in 8-byte pieces
+constexpr int kAttnKPitch = kAttnD + 8;     // K tile [key][t]: 144 B rows, 16-byte fragment reads
+constexpr int kAttnVPitch = kAttnD + 16;    // V tile [key][t]: 160 B rows (mod 128 = 32) for the transposing reads
 
 __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int qblocks) {
-  __shared__ __align__(16) bf16_t Ks[kAttnKB * kAttnKPitch];
-  __shared__ __align__(16) bf16_t Vt[kAttnD * kAttnVPitch];
+  __shared__ __align__(16) bf16_t Ks_raw[2 * kAttnKB * kAttnKPitch];
+  __shared__ __align__(16) bf16_t Vs_raw[2 * kAttnKB * kAttnVPitch];
+  lds_bf16_t* const Ks = (lds_bf16_t*)Ks_raw;
+  lds_bf16_t* const Vs = (lds_bf16_t*)Vs_raw;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-  const int half = lane / 32, lq = lane % 32;
+  const int half = lane / 32, lq = lane % 32, l16 = lane % 16;
   unsigned id = xcd_remap(blockIdx.x, gridDim.x);
   const int qb = id % qblocks;  id /= qblocks;
   const int h = id % a.heads;   id /= a.heads;
@@ -144,61 +134,92 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
     for (int r = 0; r < 16; ++r) o_acc[tb][r] = 0.f;
   float mrun = -3.0e38f, lrun = 0.f;          // lrun: this half's partial sum
 
-  for (int j0 = 0; j0 < a.S; j0 += kAttnKB) {
-    // ---- stage K[j0 .. j0+64) and V^T into LDS
+  // K and V blocks: 64 keys x 8 chunks of 16 bytes each = 2 chunks per thread per tensor
+  uint4 kreg[2], vreg[2];
+  auto fetch = [&](int j0) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      const int c = tid + t * 256;            // 64 keys x 8 chunks
-      const int key = c / 8, kc = (c % 8) * 8;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (j0 + key < a.S) v = *reinterpret_cast<const uint4*>(Kp + (long)(j0 + key) * a.stride_row + kc);
-      *reinterpret_cast<uint4*>(Ks + key * kAttnKPitch + kc) = v;
-    }
-    if (tid < 64) {
-      const int kb = (tid % 8) * 8, tc = (tid / 8) * 8;   // 8 keys x 8 features per task
-      uint32_t in[8][4];
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (j0 + kb + r < a.S) v = *reinterpret_cast<const uint4*>(Vp + (long)(j0 + kb + r) * a.stride_row + tc);
-        in[r][0] = v.x; in[r][1] = v.y; in[r][2] = v.z; in[r][3] = v.w;
-      }
-      uint4 out[8];
-      transpose_8x8_b16(in, out);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        uint2* dst = reinterpret_cast<uint2*>(Vt + (tc + e) * kAttnVPitch + kb);
-        dst[0] = make_uint2(out[e].x, out[e].y);
-        dst[1] = make_uint2(out[e].z, out[e].w);
+      const int c = tid + t * 256, key = c / 8, kc = (c % 8) * 8;
+      kreg[t] = vreg[t] = make_uint4(0, 0, 0, 0);
+      if (j0 + key < a.S) {
+        kreg[t] = *reinterpret_cast<const uint4*>(Kp + (long)(j0 + key) * a.stride_row + kc);
+        vreg[t] = *reinterpret_cast<const uint4*>(Vp + (long)(j0 + key) * a.stride_row + kc);
       }
     }
-    __syncthreads();
+  };
+  auto commit = [&](int stage) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int c = tid + t * 256, key = c / 8, kc = (c % 8) * 8;
+      lds_store16(Ks + stage * kAttnKB * kAttnKPitch + key * kAttnKPitch + kc, kreg[t]);
+      lds_store16(Vs + stage * kAttnKB * kAttnVPitch + key * kAttnVPitch + kc, vreg[t]);
+    }
+  };
+  fetch(0);
+  commit(0);
+  __syncthreads();
 
-    // ---- scores of this wave's 32 queries against the 64 staged keys, transposed
+  const int nblk = (a.S + kAttnKB - 1) / kAttnKB;
+  for (int blk = 0; blk < nblk; ++blk) {
+    const int j0 = blk * kAttnKB, cur = blk & 1;
+    if (blk + 1 < nblk) fetch(j0 + kAttnKB);
+    const lds_bf16_t* Kc = Ks + cur * kAttnKB * kAttnKPitch;
+    const lds_bf16_t* Vc = Vs + cur * kAttnKB * kAttnVPitch;
+
+    // ---- scores of this wave's 32 queries against the 64 staged keys, transposed; the two 32-key
+    // accumulators are independent and alternate in the matrix pipe
     f32x16_t s_acc[2];
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
+    for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s_acc[sb][r] = 0.f;
+    {
+      bf16x8_t kf[kAttnD / 16][2];
 #pragma unroll
-      for (int kk = 0; kk < kAttnD / 16; ++kk) {
-        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(Ks + (sb * 32 + lq) * kAttnKPitch + kk * 16 + half * 8);
-        s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s_acc[sb], 0, 0, 0);
-      }
+      for (int kk = 0; kk < kAttnD / 16; ++kk)
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+          kf[kk][sb] = *(const lds_bf16x8_t*)(Kc + (sb * 32 + lq) * kAttnKPitch + kk * 16 + half * 8);
+#pragma unroll
+      for (int kk = 0; kk < kAttnD / 16; ++kk)
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+          s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][sb], qf[kk], s_acc[sb], 0, 0, 0);
     }
     // register r of block sb is key j0 + 32 sb + 8 (r/4) + 4 half + r%4, query lane%32
+    if (mk != nullptr) {                       // uniform branch: additive key mask (in log2 units)
+      float mv[2][16];
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + sb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+          mv[sb][r] = key < a.S ? mk[key] : 0.f;
+        }
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_acc[sb][r] = fmaf(s_acc[sb][r], sc, mv[sb][r] * kLog2e);
+    } else {
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_acc[sb][r] *= sc;
+    }
+    if (j0 + kAttnKB > a.S) {                  // uniform: only the last block has keys past the end
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + sb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+          s_acc[sb][r] = key < a.S ? s_acc[sb][r] : -3.0e38f;
+        }
+    }
     float mloc = -3.0e38f;
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = j0 + sb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-        float s = s_acc[sb][r] * sc;
-        if (mk && key < a.S) s += mk[key] * kLog2e;
-        s = key < a.S ? s : -3.0e38f;
-        s_acc[sb][r] = s;
-        mloc = fmaxf(mloc, s);
-      }
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s_acc[sb][r]);
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
     const float mnew = fmaxf(mrun, mloc);
     const float corr = __builtin_amdgcn_exp2f(mrun - mnew);
@@ -214,9 +235,8 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
         for (int e = 0; e < 4; ++e) {
           const float p0 = __builtin_amdgcn_exp2f(s_acc[sb][8 * st + 2 * e] - mnew);
           const float p1 = __builtin_amdgcn_exp2f(s_acc[sb][8 * st + 2 * e + 1] - mnew);
-          const bf16_t h0 = f32_to_bf16(p0), h1 = f32_to_bf16(p1);
-          psum += bf16_to_f32(h0) + bf16_to_f32(h1);      // sum what is actually multiplied
-          w[e] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+          w[e] = pack_bf16x2(p0, p1);
+          psum += __uint_as_float(w[e] << 16) + __uint_as_float(w[e] & 0xffff0000u);   // sum what is multiplied
         }
         uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
         pf[sb][st] = __builtin_bit_cast(bf16x8_t, v);
@@ -227,20 +247,24 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[tb][r] *= corr;
 
-    // ---- O^T += V^T P^T: step (sb, st) covers keys 32 sb + 16 st + {4 half + 0..3, 8 + 4 half + 0..3}
+    // ---- O^T += V^T P^T.  Step (sb, st): k-slots 0-3 are keys 32 sb + 16 st + 4 half + 0..3, slots 4-7 the
+    // same + 8.  In a 16-lane group, lane i points at key row (i / 4), features 4 (i % 4) .. + 3 of the
+    // 4 x 16 block and receives the 4 keys of feature i.
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
         for (int tb = 0; tb < kAttnD / 32; ++tb) {
-          const bf16_t* vp = Vt + (tb * 32 + lq) * kAttnVPitch + sb * 32 + st * 16 + 4 * half;
-          const uint2 lo = *reinterpret_cast<const uint2*>(vp);
-          const uint2 hi = *reinterpret_cast<const uint2*>(vp + 8);
-          uint4 v = make_uint4(lo.x, lo.y, hi.x, hi.y);
-          o_acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, v), pf[sb][st],
+          const lds_bf16_t* vp = Vc + (sb * 32 + st * 16 + 4 * half + l16 / 4) * kAttnVPitch + tb * 32 +
+                                 ((lane / 16) % 2) * 16 + (l16 % 4) * 4;
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)vp);
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(vp + 8 * kAttnVPitch));
+          const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o_acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both), pf[sb][st],
                                                               o_acc[tb], 0, 0, 0);
         }
+    if (blk + 1 < nblk) commit(cur ^ 1);
     __syncthreads();
   }
 
@@ -253,8 +277,8 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
         uint2 v;
-        v.x = (uint32_t)f32_to_bf16(o_acc[tb][4 * rg] * inv) | ((uint32_t)f32_to_bf16(o_acc[tb][4 * rg + 1] * inv) << 16);
-        v.y = (uint32_t)f32_to_bf16(o_acc[tb][4 * rg + 2] * inv) | ((uint32_t)f32_to_bf16(o_acc[tb][4 * rg + 3] * inv) << 16);
+        v.x = pack_bf16x2(o_acc[tb][4 * rg] * inv, o_acc[tb][4 * rg + 1] * inv);
+        v.y = pack_bf16x2(o_acc[tb][4 * rg + 2] * inv, o_acc[tb][4 * rg + 3] * inv);
         *reinterpret_cast<uint2*>(Op + tb * 32 + 8 * rg + 4 * half) = v;
       }
   }

@@ -327,7 +327,7 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
         for (int e = 0; e < 4; ++e) {
           const float a0 = act_const<ACT2>(v[2 * e] + __uint_as_float(w[e] << 16));
           const float a1 = act_const<ACT2>(v[2 * e + 1] + __uint_as_float(w[e] & 0xffff0000u));
-          o[e] = (uint32_t)f32_to_bf16(a0) | ((uint32_t)f32_to_bf16(a1) << 16);
+          o[e] = pack_bf16x2(a0, a1);
         }
         *reinterpret_cast<uint4*>(C + off[t]) = make_uint4(o[0], o[1], o[2], o[3]);
       } else {

@@ -23,8 +23,8 @@ template <> struct VecIO<bf16_t, 4> {
   }
   static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[4]) {
     uint2 t;
-    t.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-    t.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+    t.x = pack_bf16x2(v[0], v[1]);
+    t.y = pack_bf16x2(v[2], v[3]);
     *reinterpret_cast<uint2*>(p) = t;
   }
 };
