@@ -61,7 +61,6 @@ struct Epilogue {
   int act;
   int act_before_residual;  // matmul: act(.) + residual;  convolution: act(. + residual)
   int vec_store;            // C (and residual) rows are 16-byte aligned and cols % 8 == 0
-  int dbg;                  // TEMPORARY probe flags
 };
 
 // ------------------------------------------------------------------------------------------

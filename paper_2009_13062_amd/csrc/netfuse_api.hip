@@ -89,6 +89,8 @@ int pick_dma(int rows, int cols, int K, long long problems) {
   // measured on MI355X: 256x256 tiles win once there are >= 4 workgroups per CU, otherwise 128x128
   // tiles with a 32-deep k-step, 8 waves and 4 stages (two workgroups per CU)
   if (fits(D256x256k32s4) && problems * (rows / 256) * (cols / 256) >= 1024) return D256x256k32s4;
+  // one row tile and a long K: 64-deep k-steps fetch whole 128-byte lines of the activation rows
+  if (rows == 128 && K >= 2048 && fits(D128x128k64s3w8)) return D128x128k64s3w8;
   if (fits(D128x128k32s4)) return D128x128k32s4;
   return -1;
 }
@@ -166,7 +168,6 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     a.ep.col_bias = bias; a.ep.col_vec_stride0 = Nout;
     a.ep.act = act; a.ep.act_before_residual = 1;
     a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16);
-    { static const int dbg = getenv("NETFUSE_DBG") ? atoi(getenv("NETFUSE_DBG")) : 0; a.ep.dbg = dbg; }
     if (bkind == 8 && al == 16) {
       const int d = pick_dma(N, Nout, K, M);
       if (d >= 0) return launch_gemm_dma(d, L, s);

@@ -494,3 +494,55 @@ def test_resnet_full_size_sampled(nf, oracle, name, M, card, bw, cfg):
     out = net.forward(inp["x"])
     assert torch.isfinite(out.float()).all()
     _resnet_per_call_parity(oracle, net, inp["x"], spec, [M - 1])
+
+
+# ------------------------------------------------------------------ degenerate and extreme shapes
+@pytest.mark.parametrize("dtype", DTYPES, ids=ids)
+def test_degenerate_shapes(nf, oracle, dtype):
+    """Single rows, single features, single keys, one-pixel images, depthwise groups."""
+    bf = dtype == torch.bfloat16
+    for (M, N, K, Nout) in [(1, 1, 1, 1), (3, 1, 8, 8), (2, 9, 1, 16), (2, 16, 64, 1)]:
+        X, W, b = grid(rnd(M, N, K), dtype), grid(rnd(M, K, Nout), dtype), rnd(M, Nout)
+        check(host(nf.linear(dev(X, dtype), dev(W, dtype), bias=dev(b))),
+              oracle.linear(X, W, bias=b, out_bf16=bf), dtype, "linear %s" % ((M, N, K, Nout),))
+    # H = 1: the variance is zero, the output is beta; rows = 1
+    x, g, b = grid(rnd(3, 1, 1), dtype), rnd(3), rnd(3)
+    check(host(nf.layernorm(dev(x, dtype), dev(g), dev(b), 3)), oracle.layernorm(x, g, b, 3, out_bf16=bf), dtype, "LN H=1")
+    # one key: softmax is 1, O = V; head dim 1
+    for (S, heads, d) in [(1, 2, 64), (1, 1, 1), (5, 2, 1)]:
+        qkv = grid(rnd(2, S, 3 * heads * d), dtype)
+        check(host(nf.attention_packed(dev(qkv, dtype), 1, S, heads)),
+              oracle.attention_packed(qkv, 1, S, heads, out_bf16=bf), dtype, "attention S=%d d=%d" % (S, d))
+    # 1x1 image with a 3x3 kernel and padding; depthwise (one channel per group); 1x1 image pointwise
+    for (M, Cin, Cout, g_, H, k, pad) in [(2, 16, 16, 1, 1, 3, 1), (2, 8, 8, 8, 5, 3, 1), (3, 4, 6, 2, 1, 1, 0)]:
+        x = grid(rnd(1, M * Cin, H, H), dtype)
+        w = grid(rnd(M * Cout, Cin // g_, k, k, std=0.3), dtype)
+        check(host(nf.conv2d(dev(x, dtype), dev(w, dtype), M, g=g_, pad=pad)),
+              oracle.conv2d(x, w, M, g=g_, pad=pad, out_bf16=bf), dtype, "conv %s" % ((M, Cin, Cout, g_, H, k),))
+    x = grid(rnd(1, 6, 1, 1), dtype)
+    assert np.array_equal(host(nf.maxpool2d(dev(x, dtype), 3, 2, 1)), oracle.maxpool2d(x, 3, 2, 1))
+    check(host(nf.avgpool_global(dev(x, dtype))), oracle.avgpool_global(x, out_bf16=bf), dtype, "avgpool HW=1")
+
+
+def test_many_small_problems_and_long_rows(nf, oracle):
+    """Grid-size extremes: 4096 models of a tiny matmul; one LayerNorm row of 65536 features."""
+    M = 4096
+    X, W = NI.on_bf16_grid(rnd(M, 4, 16)), NI.on_bf16_grid(rnd(M, 16, 8, std=0.25))
+    check(host(nf.linear(dev(X, torch.bfloat16), dev(W, torch.bfloat16))), oracle.linear(X, W, out_bf16=True),
+          torch.bfloat16, "4096 models")
+    H = 65536
+    x, g, b = rnd(1, 2, H), rnd(H, mean=1.0, std=0.1), rnd(H, std=0.1)
+    check(host(nf.layernorm(dev(x), dev(g), dev(b), 1)), oracle.layernorm(x, g, b, 1), torch.float32, "LN H=65536")
+
+
+def test_errors_leave_outputs_untouched(nf):
+    """A rejected call enqueues nothing."""
+    X = torch.zeros(2, 4, 8, device="cuda", dtype=torch.bfloat16)
+    W = torch.zeros(2, 8, 8, device="cuda", dtype=torch.bfloat16)
+    Y = torch.full((2, 4, 8), 7.0, device="cuda", dtype=torch.bfloat16)
+    st = nf.lib.netfuse_linear(X.data_ptr(), W.data_ptr(), None, None, Y.data_ptr(), 2, 4, 8, 8, 1, 99, None)
+    assert st == nf.NF_EINVAL
+    with pytest.raises(nf.NetFuseError):
+        nf.conv2d(torch.zeros(1, 6, 4, 4, device="cuda"), torch.zeros(6, 3, 3, 3, device="cuda"), 2, dil=0)
+    torch.cuda.synchronize()
+    assert torch.all(Y == 7.0)
