@@ -15,6 +15,12 @@
 // then overwrites only the in-image pixels.  Image column ix lives at patch column ix + kLPad (8), so a
 // row is copied as W / VW aligned chunks of VW pixels on both the global and the LDS side.
 //
+// Narrow groups (ResNeXt: 4, 8 or 16 channels per group): S = 32 / cig consecutive groups are fused
+// into one 32-channel block whose weight tile is block diagonal (row r of the tile carries the cig*KHW
+// weights of its own group at column offset (r / cog)*cig*KHW, zeros elsewhere).  The MFMA then
+// multiplies S times more zeros than data, which is free next to the HBM traffic of such layers, and
+// no product ever crosses a group: group isolation is exact, not approximate.
+//
 // One workgroup = one (image, group, 128-position tile, BM output channels).  Accumulators and the
 // fused epilogue (folded batch norm scale/shift, residual, ReLU) are those of gemm_mfma.h.
 #pragma once
@@ -31,6 +37,8 @@ struct ConvPatchArgs {
   int cig, cog, nG, H, W, Ho, Wo, HoWo, stride, pad;
   int PW, PS;                 // patch row pitch and plane pitch (elements); PS covers the tallest patch
   int VW, cpr;                // patch rows are copied in chunks of VW pixels (VW | W, power of two <= 8); cpr = W / VW
+  int S;                      // groups fused per workgroup (see below); 1 = one group per workgroup
+  int cig_real, cog_real;     // S > 1: channels of ONE group; cig = S*cig_real, cog = S*cog_real then describe the fused group
   int tiles_m, tiles_n;
   long x_group, x_image, y_group, y_image;   // element strides
   Epilogue ep;
@@ -83,7 +91,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
   const int PH = (p_last / a.Wo - oy_first) * a.stride + Cfg::kKH;   // rows actually needed (<= PS / PW)
   const int iy0 = oy_first * a.stride - a.pad;
   const bf16_t* xg = a.x + (long)b * a.x_image + (long)G * a.x_group;
-  const bf16_t* wg = a.w + ((long)G * a.cog + row0) * a.cig * KHW;
+  const bf16_t* wg = a.w + ((long)G * a.cog + row0) * a.cig * KHW;        // S == 1: dense rows of cig*KHW weights
 
   // ---- per-lane gather bases: patch offset of this lane's output position, per column block
   int pix[FN];
@@ -134,7 +142,7 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
     for (int t = 0; t < kAPer; ++t) {
       const int c = tid + t * 256, r = c / kCpr, ch = c - r * kCpr;
       va[t] = make_uint4(0, 0, 0, 0);
-      if ((kAChunks % 256 == 0 || c < kAChunks) && r < rows_left)
+      if (a.S == 1 && (kAChunks % 256 == 0 || c < kAChunks) && r < rows_left)
         va[t] = *reinterpret_cast<const uint4*>(wg + ((long)r * a.cig + ci0) * KHW + ch * 8);
     }
     const bf16_t* xc = xg + (long)ci0 * a.H * a.W;
@@ -151,14 +159,29 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
     }
   };
   prefetch(0);
-  __syncthreads();                                         // the zero fill is complete
+  if (a.S > 1) {
+    // block-diagonal weight tile of S fused groups (single channel block): zero it, then drop each
+    // row's cig_real*KHW weights (8-byte chunks) at its group's column offset
+    for (int c = tid; c < Cfg::kBM * Cfg::kAPitch / 8; c += 256) lds_store16(As + c * 8, make_uint4(0, 0, 0, 0));
+    __syncthreads();
+    const int klen = a.cig_real * KHW, cpw = klen / 4;       // weights per row, 4-element chunks per row
+    const bf16_t* ws = a.w + (long)G * a.cog * klen;         // fused group G: rows G*cog .. of the weight tensor
+    for (int c = tid; c < a.cog * cpw; c += 256) {
+      const int r = c / cpw, ch = c - r * cpw;
+      const uint2 v = *reinterpret_cast<const uint2*>(ws + (long)r * klen + ch * 4);
+      lds_store8(As + r * Cfg::kAPitch + (r / a.cog_real) * klen + ch * 4, v.x, v.y);
+    }
+  }
+  __syncthreads();                                         // the zero fills are complete
 
   for (int ci0 = 0; ci0 < a.cig; ci0 += CB) {
     // ---- commit the prefetched block to LDS
+    if (a.S == 1) {
 #pragma unroll
-    for (int t = 0; t < kAPer; ++t) {
-      const int c = tid + t * 256, r = c / kCpr, ch = c - r * kCpr;
-      if (kAChunks % 256 == 0 || c < kAChunks) lds_store16(As + r * Cfg::kAPitch + ch * 8, va[t]);
+      for (int t = 0; t < kAPer; ++t) {
+        const int c = tid + t * 256, r = c / kCpr, ch = c - r * kCpr;
+        if (kAChunks % 256 == 0 || c < kAChunks) lds_store16(As + r * Cfg::kAPitch + ch * 8, va[t]);
+      }
     }
 #pragma unroll
     for (int u = 0; u < kNT; ++u) {

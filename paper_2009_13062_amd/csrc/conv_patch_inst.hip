@@ -32,6 +32,7 @@ static nf_status launch_one(ConvPatchArgs& a, int B, hipStream_t s) {
 
 // 3x3, dilation 1, cig % 16 == 0, patch width <= 64.  The caller has filled everything but the tiling.
 nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
+  if (a.S > 1) return launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4>>(a, B, s);   // fused narrow groups: one 32-channel block
   // the tallest row tile that still gives every CU two workgroups
   const long long per_row_tile = (long long)((a.HoWo + 127) / 128) * a.nG * B;
   auto tiles = [&](int bm) { return per_row_tile * ((a.cog + bm - 1) / bm); };

@@ -253,20 +253,30 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     const int PWp = (maxcol + 1 + 7) / 8 * 8;
     const int span = (int)std::min<long long>(Ho, (126 + Wo) / Wo + 1);
     const int PHmax = (span - 1) * stride + KH;
-    const long long patch_tasks = 16LL * PHmax * (W / VW);          // chunk copies per 16-channel block
-    if (!no_patch && KH == 3 && KW == 3 && dilation == 1 && cig % 16 == 0 && pad <= kLPad && patch_tasks <= 12 * 256 &&
-        aligned(w, 16) && aligned(x, 16)) {
+    // narrow groups: fuse S = 32 / cig consecutive groups into one 32-channel block (block-diagonal weights)
+    int S = 1;
+    if (cig < 32 && 32 % cig == 0 && cig % 4 == 0 && (long long)(32 / cig) * cog <= 32 && (M * g) % (32 / cig) == 0 &&
+        aligned(w, 8))
+      S = 32 / cig;
+    const int cig_e = S * cig, cog_e = S * cog;               // channels of the (fused) group a workgroup handles
+    const long long patch_tasks = (long long)std::min(cig_e, 16) * PHmax * (W / VW);   // chunk copies per channel block
+    const bool patch_ok = KH == 3 && KW == 3 && dilation == 1 && pad <= kLPad && aligned(x, 16) &&
+                          ((S == 1 && cig % 16 == 0 && aligned(w, 16) && patch_tasks <= 12 * 256) ||
+                           (S > 1 && 2 * patch_tasks <= 12 * 256));
+    if (!no_patch && patch_ok) {
       // k x k: gather MFMA operands from an LDS copy of the zero-padded input patch (conv_patch.h)
       ConvPatchArgs c;
       memset(&c, 0, sizeof(c));
       c.x = (const bf16_t*)x; c.w = (const bf16_t*)w; c.R = (const bf16_t*)residual; c.y = (bf16_t*)y;
-      c.cig = cig; c.cog = cog; c.nG = M * g; c.H = H; c.W = W; c.Ho = (int)Ho; c.Wo = (int)Wo; c.HoWo = HoWo;
+      c.cig = cig_e; c.cog = cog_e; c.nG = M * g / S; c.S = S; c.cig_real = cig; c.cog_real = cog;
+      c.H = H; c.W = W; c.Ho = (int)Ho; c.Wo = (int)Wo; c.HoWo = HoWo;
       c.stride = stride; c.pad = pad;
       c.PW = PWp; c.VW = VW; c.cpr = W / VW;
       c.PS = PHmax * PWp;               // padded per kernel configuration at launch
-      c.x_group = (long)cig * H * W; c.x_image = (long)Ctot_in * H * W;
-      c.y_group = (long)cog * HoWo; c.y_image = (long)Ctot_out * HoWo;
+      c.x_group = (long)cig_e * H * W; c.x_image = (long)Ctot_in * H * W;
+      c.y_group = (long)cog_e * HoWo; c.y_image = (long)Ctot_out * HoWo;
       c.ep = a.ep;
+      c.ep.row_vec_stride0 = cog_e;
       return launch_conv_patch_3x3(c, B, s);
     }
     a.geom.H = H; a.geom.W = W; a.geom.KH = KH; a.geom.KW = KW; a.geom.Wo = (int)Wo;

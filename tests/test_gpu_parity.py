@@ -149,6 +149,9 @@ CONV_CASES = [
     (1, 1, 64, 64, 1, 56, 56, 3, 3, 1, 1, 1),      # patch-gather, 58-wide patch, tiles that start mid-row
     (2, 1, 64, 128, 1, 30, 30, 3, 3, 2, 1, 1),     # patch-gather, stride 2, odd output width 15
     (2, 1, 48, 64, 1, 12, 12, 3, 3, 1, 0, 1),      # patch-gather, no padding, 3 channel blocks
+    (3, 1, 64, 64, 8, 28, 28, 3, 3, 1, 1, 1),      # fused narrow groups: 8 channels per group, 4 groups per block
+    (2, 2, 64, 64, 4, 16, 16, 3, 3, 2, 1, 1),      # fused narrow groups: 16 per group, stride 2, batch 2
+    (1, 1, 32, 32, 8, 56, 56, 3, 3, 1, 1, 1),      # fused narrow groups: 4 per group on a 56x56 image
 ]
 
 
