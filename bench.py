@@ -105,20 +105,38 @@ class OpTimer:
         for k, v in self.saved.items():
             setattr(self.nf, k, v)
 
+    def empty_pairs(self, n=64):
+        """Event pairs around nothing, recorded in the middle of the same stream of work: what a
+        start/stop pair measures by itself (subtracted from every bracketed launch)."""
+        torch = self.torch
+        self.empty = []
+        for _ in range(n):
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record()
+            e.record()
+            self.empty.append((s, e))
+
     def summary(self):
         self.torch.cuda.synchronize()
+        self.overhead_ms = 0.0
+        if getattr(self, "empty", None):
+            vals = sorted(s.elapsed_time(e) for s, e in self.empty)
+            self.overhead_ms = vals[0]            # the smallest: never over-corrects
         agg = {}
         for tag, s, e, fl, by in self.records:
             a = agg.setdefault(tag, dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
             a["launches"] += 1
-            a["ms"] += s.elapsed_time(e)
+            a["ms"] += max(s.elapsed_time(e) - self.overhead_ms, 1e-4)
             a["flops"] += fl
             a["bytes"] += by
         return agg
 
 
 def group_family(tag):
-    return tag.split("_")[0]
+    """Kernel family of an op tag: every convolution shape runs in the same two kernel templates
+    (gemm_mfma_kernel / conv_patch_kernel), every matmul in gemm_dma_kernel / gemm_mfma_kernel."""
+    head = tag.split("_")[0]
+    return "conv" if head.startswith("conv") else head
 
 
 def roofline_for(agg):
@@ -268,9 +286,13 @@ def run_workload(name, steps, warmup, use_graph, torch, nf, sep_steps=None, sepa
         res["separate_ms"] = res["separate_inferences_per_s"] = res["speedup_vs_separate"] = None
     # per-kernel pass: the same steps, un-graphed, HIP events around every launch
     with OpTimer(nf, torch) as ot:
-        for _ in range(max(3, min(steps, 10))):
+        npass = max(3, min(steps, 10))
+        for i in range(npass):
             merged()
+            if i == npass // 2:
+                ot.empty_pairs()
         agg = ot.summary()
+    res["event_pair_overhead_us"] = 1e3 * ot.overhead_ms
     res["kernels"] = {k: dict(launches=v["launches"], avg_us=1e3 * v["ms"] / v["launches"],
                               GBps=v["bytes"] / (v["ms"] * 1e-3) / 1e9, TFLOPs=v["flops"] / (v["ms"] * 1e-3) / 1e12)
                       for k, v in sorted(agg.items(), key=lambda kv: -kv[1]["ms"])}
@@ -378,6 +400,7 @@ def main():
         "speedup_vs_separate": head["speedup_vs_separate"],
         "launch": {k: head[k] for k in ("eager_ms", "graph_ms", "separate_eager_ms", "separate_graph_ms", "graph_error") if k in head},
         "model_TFLOPs": head["model_TFLOPs"],
+        "event_pair_overhead_us": head["event_pair_overhead_us"],
         "roofline": {k: rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "launches",
                                         "avg_us", "bytes_per_launch", "flops_per_launch", "frac_hbm", "frac_mfma",
                                         "frac_of_min_roof")},

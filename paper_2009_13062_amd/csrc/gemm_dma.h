@@ -44,8 +44,8 @@ struct DmaCfg {
   static constexpr int kLdsPipe = NS * kStageBytes;
   static constexpr int kLdsBytes = kLdsPipe > kLdsEpi ? kLdsPipe : kLdsEpi;
   static constexpr int kACpr = BK / 8, kARpi = 64 / kACpr;              // A: chunks per row, rows per instruction
-  static constexpr int kBCpr = BN / 8, kBRpi = 64 / kBCpr;              // B: likewise
-  static_assert(kBRpi >= 1, "BN <= 512");
+  static constexpr int kBCpr = BN / 8;                                  // B: chunks per row (rows need not divide 64)
+  static_assert(BN % 32 == 0, "whole 32-column MFMA blocks");
   __device__ static __forceinline__ int swz_a(int row) { return (row * kACpr / 8) % kACpr; }
 };
 
@@ -75,8 +75,9 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
   }
 #pragma unroll
   for (int t = 0; t < Cfg::kBInstr; ++t) {
-    const int krow = (t * Cfg::kNW + wave) * Cfg::kBRpi + lane / Cfg::kBCpr;
-    const int c = (lane % Cfg::kBCpr) ^ (2 * (krow % 4));
+    const int flat = (t * Cfg::kNW + wave) * 64 + lane;      // chunk index in the row-major [BK][BN] LDS tile
+    const int krow = flat / Cfg::kBCpr;
+    const int c = (flat % Cfg::kBCpr) ^ (2 * (krow % 4));     // stays inside the row: BN/8 is a multiple of 4
     b_src[t] = (long)krow * ldb + c * 8;
   }
   auto issue_stage = [&](int kt) {

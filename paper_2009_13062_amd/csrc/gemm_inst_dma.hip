@@ -60,6 +60,9 @@ nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s) {
     case D128x64k32s4w4: return launch_dma<DmaCfg<128, 64, 32, 4, 1, 4>>(L, s);
     case D64x128k64s4w4: return launch_dma<DmaCfg<64, 128, 64, 1, 4, 4>>(L, s);
     case D128x128k64s3w8: return launch_dma<DmaCfg<128, 128, 64, 2, 4, 3>>(L, s);
+    case D128x192k32s4w4: return launch_dma<DmaCfg<128, 192, 32, 2, 2, 4>>(L, s);
+    case D128x192k32s3w4: return launch_dma<DmaCfg<128, 192, 32, 2, 2, 3>>(L, s);
+    case D128x192k64s3w8: return launch_dma<DmaCfg<128, 192, 64, 4, 2, 3>>(L, s);
   }
   return NF_EUNSUPPORTED;
 }

@@ -95,20 +95,20 @@ int pick_dma(int rows, int cols, int K, long long problems) {
   return -1;
 }
 
-// Tile choice.  Measured on MI355X: with one k-step of prefetch the kernel is bound by load latency,
-// and 8 wavefronts on a 128x128 tile (3 workgroups per CU) hide it best; small problems take the
-// smallest tile that covers them.
+// Tile choice for the register-staged kernels.  With one k-step of prefetch these kernels are bound by
+// load latency, so the first goal is two workgroups per CU (512 tiles); among the tiles that reach it the
+// largest wins, and 8 wavefronts on a 128x128 tile hide latency best.
 int pick_tile(int rows, int cols, long long problems) {
   const int f = forced_tile();
   if (f >= 0) return f;
-  if (rows <= 32) return T32x128;
-  if (rows <= 64) return cols <= 64 ? T64x64 : T64x128;
-  if (cols <= 64) return T64x64;
   auto tiles = [&](int t) {
     return problems * ((rows + kTileBM[t] - 1) / kTileBM[t]) * ((cols + kTileBN[t] - 1) / kTileBN[t]);
   };
-  if (tiles(T128x128w8) >= 256) return T128x128w8;
-  return T64x128;
+  if (rows <= 32) return T32x128;
+  if (cols <= 64) return T64x64;
+  if (rows > 64 && tiles(T128x128w8) >= 512) return T128x128w8;
+  if (tiles(T64x128) >= 512) return T64x128;
+  return T32x128;
 }
 
 // largest alignment (16, 8, 4 or 2 bytes) shared by a pointer and a row pitch / stride set
