@@ -95,7 +95,8 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a) {
 constexpr int kAttnD = 64;
 constexpr int kAttnKB = 64;                 // keys per LDS stage
 constexpr int kAttnKPitch = kAttnD + 8;     // K tile [key][t]: 144 B rows, 16-byte fragment reads
-constexpr int kAttnVPitch = kAttnD + 16;    // V tile [key][t]: 160 B rows (mod 128 = 32) for the transposing reads
+constexpr int kAttnVPitch = kAttnD + 32;    // V tile [key][t]: 192 B rows, so the 4 keys x 64 B that 32 lanes of a
+                                            // transposing read touch tile the 256 bytes of the 64 LDS banks
 
 __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int qblocks) {
   __shared__ __align__(16) bf16_t Ks_raw[2 * kAttnKB * kAttnKPitch];

@@ -29,8 +29,7 @@
 namespace nf {
 
 constexpr int kLPad = 8;     // patch column of image column 0
-constexpr int kHalfShift = 32;   // extra elements before the upper half of a block's planes: with plane pitches that
-                                 // are multiples of 8 the two lane halves then read opposite halves of the LDS banks
+constexpr int kHalfShiftMax = 64; // see ConvPatchCfg::half_shift
 
 struct ConvPatchArgs {
   const bf16_t* x; const bf16_t* w; const bf16_t* R; bf16_t* y;
@@ -61,8 +60,13 @@ struct ConvPatchCfg {
   static constexpr int kEpiPitch = kBN + 4;
   static constexpr int kLdsEpi = WGM * 32 * kEpiPitch * (int)sizeof(float);
   static constexpr int kPatchTasksMax = 12 * 256;
+  // Extra elements before the upper half of a block's planes, chosen so that the two lane halves of a
+  // gather read addresses 128 bytes apart modulo the 256 bytes of the 64 LDS banks (plane pitches are
+  // multiples of 8 elements, so CB/2 planes are a multiple of 128 bytes).
+  __host__ __device__ static constexpr int half_shift(int PS) { return ((CB / 2) * PS) % 128 == 0 ? 64 : 0; }
+  static_assert(CB % 16 == 0, "half_shift assumes CB/2 planes of 8-element granularity span whole 128-byte units");
   static constexpr int lds_bytes(int PS) {
-    const int pipe = kABytes + (CB * PS + kHalfShift) * 2;
+    const int pipe = kABytes + (CB * PS + kHalfShiftMax) * 2;
     return pipe > kLdsEpi ? pipe : kLdsEpi;
   }
 };
@@ -94,12 +98,13 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
   const bf16_t* wg = a.w + ((long)G * a.cog + row0) * a.cig * KHW;        // S == 1: dense rows of cig*KHW weights
 
   // ---- per-lane gather bases: patch offset of this lane's output position, per column block
+  const int hshift = Cfg::half_shift(a.PS);
   int pix[FN];
 #pragma unroll
   for (int j = 0; j < FN; ++j) {
     const int p = min(p0 + wn * Cfg::WN + j * 32 + l32, p_last);     // clamp: columns past the end are discarded
     const int oy = p / a.Wo, ox = p - oy * a.Wo;
-    pix[j] = ((oy - oy_first) * a.stride) * a.PW + ox * a.stride + (kLPad - a.pad) + half * ((CB / 2) * a.PS + kHalfShift);
+    pix[j] = ((oy - oy_first) * a.stride) * a.PW + ox * a.stride + (kLPad - a.pad) + half * ((CB / 2) * a.PS + hshift);
   }
   const int a_off = (wm * Cfg::WM + l32) * Cfg::kAPitch + half * Cfg::kHalfK;
 
@@ -127,11 +132,11 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
       const int iy = iy0 + py;
       const bool live = task < ntasks && iy >= 0 && iy < a.H;
       g_off[u] = live ? (ci * a.H + iy) * a.W + ch * a.VW : -1;
-      l_off[u] = ci * a.PS + (ci >= CB / 2 ? kHalfShift : 0) + py * a.PW + kLPad + ch * a.VW;
+      l_off[u] = ci * a.PS + (ci >= CB / 2 ? hshift : 0) + py * a.PW + kLPad + ch * a.VW;
     }
   }
   // zero the whole patch once: padding and out-of-image rows are never written again
-  for (int c = tid; c < (CB * a.PS + kHalfShift) / 8; c += 256) lds_store16(Ps + c * 8, make_uint4(0, 0, 0, 0));
+  for (int c = tid; c < (CB * a.PS + kHalfShiftMax) / 8; c += 256) lds_store16(Ps + c * 8, make_uint4(0, 0, 0, 0));
 
   // ---- software pipeline over channel blocks: the global loads of block s+1 are in flight in
   // registers while block s is multiplied out of LDS

@@ -8,12 +8,12 @@
 // staging and NS-1 k-steps can be in flight per workgroup.  Because the LDS side of such a load is
 // fixed (lane l -> byte 16 l of the 1 KB block), bank conflicts are avoided by permuting WHICH global
 // 16-byte chunk a lane fetches (an XOR swizzle), not where it lands:
-//   A tile [BM][BK] (k contiguous): chunk c of row r is stored at position c ^ s(r), s(r) = r % 8 for
-//     128-byte rows, (r / 2) % 4 for 64-byte rows, so the 8 rows hit by 8 neighbouring lanes of a
-//     16-byte fragment read fall into 8 distinct 16-byte bank groups.
-//   B tile [BK][BN] (column contiguous): chunk c of row k is stored at position c ^ 2 (k % 4), so the
-//     4 rows x 32 bytes touched by one 16-lane group of a transposing read (ds_read_b64_tr_b16)
-//     fall into distinct bank groups.
+//   A tile [BM][BK] (k contiguous): chunk c of row r is stored at position c ^ s(r), s(r) = (r / 2) % 8
+//     for 128-byte rows, (r / 4) % 4 for 64-byte rows, so the 16 rows hit by 16 neighbouring lanes of a
+//     16-byte fragment read cover all 16 16-byte groups of the 64 banks.
+//   B tile [BK][BN] (column contiguous): chunk c of row k is stored at position c ^ 4 (k % 4), so the
+//     4 rows x 64 bytes touched by 32 neighbouring lanes of a transposing read (ds_read_b64_tr_b16)
+//     fall into distinct banks.
 // Waiting is explicit: a thread's loads retire in order, so "stage kt has landed" is
 // s_waitcnt vmcnt(loads issued after it); a workgroup barrier then publishes every thread's share
 // and, at the same time, proves that the stage read in the previous step is free to be refilled.
@@ -46,7 +46,12 @@ struct DmaCfg {
   static constexpr int kACpr = BK / 8, kARpi = 64 / kACpr;              // A: chunks per row, rows per instruction
   static constexpr int kBCpr = BN / 8;                                  // B: chunks per row (rows need not divide 64)
   static_assert(BN % 32 == 0, "whole 32-column MFMA blocks");
-  __device__ static __forceinline__ int swz_a(int row) { return (row * kACpr / 8) % kACpr; }
+  // LDS serves 256 bytes per clock (64 banks): a 16-byte read is processed 16 lanes at a time, a
+  // transposing 8-byte read 32 lanes at a time, and the lanes of one such group must cover distinct banks.
+  static constexpr int kARowsPer256 = 256 / kARow;                      // A rows that share one bank span
+  __device__ static __forceinline__ int swz_a(int row) { return (row / kARowsPer256) % kACpr; }
+  static_assert(kBCpr % 16 == 0, "B rows are permuted in units of 16 chunks");
+  static constexpr int kBSwz = 4;                                       // chunk ^= 4 (k % 4) stays in the row
 };
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0 and
@@ -54,6 +59,11 @@ struct DmaCfg {
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+// only the LDS / scalar-memory counter constrained (vmcnt left at its maximum)
+__device__ __forceinline__ void wait_lgkmcnt0() {
+  __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8));
 }
 
 template <class Cfg>
@@ -77,7 +87,7 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
   for (int t = 0; t < Cfg::kBInstr; ++t) {
     const int flat = (t * Cfg::kNW + wave) * 64 + lane;      // chunk index in the row-major [BK][BN] LDS tile
     const int krow = flat / Cfg::kBCpr;
-    const int c = (flat % Cfg::kBCpr) ^ (2 * (krow % 4));     // stays inside the row: BN/8 is a multiple of 4
+    const int c = (flat % Cfg::kBCpr) ^ (Cfg::kBSwz * (krow % 4));
     b_src[t] = (long)krow * ldb + c * 8;
   }
   auto issue_stage = [&](int kt) {
@@ -97,14 +107,14 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
   int a_off[FM], b_off[FN][2];
 #pragma unroll
   for (int i = 0; i < FM; ++i) a_off[i] = (wm * Cfg::WM + i * 32 + l32) * Cfg::kARow;
-  const int a_swz = Cfg::swz_a(l32);                  // row offsets above are multiples of 8: same swizzle
+  const int a_swz = Cfg::swz_a(l32);                  // row offsets above are multiples of 32: same swizzle
 #pragma unroll
   for (int j = 0; j < FN; ++j)
 #pragma unroll
     for (int hl = 0; hl < 2; ++hl) {
       const int kr = 8 * half + l16 / 4 + 4 * hl;     // row inside a 16-k step; kr % 4 = l16 / 4
       const int n = wn * Cfg::WN + j * 32 + ((lane / 16) % 2) * 16 + (l16 % 4) * 4;
-      b_off[j][hl] = Cfg::kABytes + kr * Cfg::kBRow + (((n / 8) ^ (2 * (l16 / 4))) * 16) + ((n / 4) % 2) * 8;
+      b_off[j][hl] = Cfg::kABytes + kr * Cfg::kBRow + (((n / 8) ^ (Cfg::kBSwz * (l16 / 4))) * 16) + ((n / 4) % 2) * 8;
     }
 
   f32x16_t acc[FM][FN];
@@ -125,35 +135,36 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
     // end fewer stages were issued, so wait for everything.
     if (kt + NS - 2 < nk) wait_vmcnt<Cfg::kInFlight>(); else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
-    if (kt + NS - 1 < nk) issue_stage(kt + NS - 1);   // refills the stage read in step kt-1
     const lds_u8_t* stage = smem + (kt % NS) * Cfg::kStageBytes;
-    // fragments are double buffered: those of 16-k step kk+1 are requested before the MFMAs of
-    // step kk issue, so LDS latency hides behind the matrix pipe
-    bf16x8_t af[2][FM], bfr[2][FN];
-    auto load_frags = [&](int kk, bf16x8_t (&a)[FM], bf16x8_t (&b)[FN]) {
+    // All fragments of the k-step are read BEFORE the next stage's loads are issued: LDS reads that a
+    // wave issues behind its own fresh direct-to-LDS loads are held up by them (measured: 20 % of the
+    // kernel on weight-streaming shapes), whereas the loads lose nothing by starting one LDS latency later.
+    bf16x8_t af[BK / 16][FM], bfr[BK / 16][FN];
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
 #pragma unroll
       for (int i = 0; i < FM; ++i)
-        a[i] = *(const lds_bf16x8_t*)(stage + a_off[i] + (((2 * kk + half) ^ a_swz) * 16));
+        af[kk][i] = *(const lds_bf16x8_t*)(stage + a_off[i] + (((2 * kk + half) ^ a_swz) * 16));
 #pragma unroll
       for (int j = 0; j < FN; ++j) {
         const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][0] + kk * 16 * Cfg::kBRow));
         const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][1] + kk * 16 * Cfg::kBRow));
         const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        b[j] = __builtin_bit_cast(bf16x8_t, both);
+        bfr[kk][j] = __builtin_bit_cast(bf16x8_t, both);
       }
-    };
-    load_frags(0, af[0], bfr[0]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    wait_lgkmcnt0();
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt + NS - 1 < nk) issue_stage(kt + NS - 1);   // refills the stage read in step kt-1
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) load_frags(kk + 1, af[(kk + 1) & 1], bfr[(kk + 1) & 1]);
-      __builtin_amdgcn_sched_barrier(0);     // keep the next step's LDS reads ahead of this step's MFMAs
+    for (int kk = 0; kk < BK / 16; ++kk)
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
   }
   __syncthreads();   // every wave is done with the last stage before the epilogue reuses LDS
   gemm_epilogue<Cfg>(acc, (lds_f32_t*)smem, C, R, ldc, Cfg::kBM, Cfg::kBN, ep, row_vec_off, col_vec_off);

@@ -85,13 +85,9 @@ template <int ALIGN_A, int BKIND>
 nf_status launch_gemm_tile(int tile, GemmLaunch& L, hipStream_t s) {
   switch (tile) {
     case T128x128: return launch_gemm<TileCfg<128, 128, 2, 2>, ALIGN_A, BKIND>(L, s);
-    case T128x256: return launch_gemm<TileCfg<128, 256, 2, 2>, ALIGN_A, BKIND>(L, s);
-    case T256x128: return launch_gemm<TileCfg<256, 128, 2, 2>, ALIGN_A, BKIND>(L, s);
     case T64x128: return launch_gemm<TileCfg<64, 128, 2, 2>, ALIGN_A, BKIND>(L, s);
     case T64x64: return launch_gemm<TileCfg<64, 64, 2, 2>, ALIGN_A, BKIND>(L, s);
     case T32x128: return launch_gemm<TileCfg<32, 128, 1, 4>, ALIGN_A, BKIND>(L, s);
-    case T256x256w8: return launch_gemm<TileCfg<256, 256, 2, 4>, ALIGN_A, BKIND>(L, s);
-    case T128x256w8: return launch_gemm<TileCfg<128, 256, 2, 4>, ALIGN_A, BKIND>(L, s);
     case T128x128w8: return launch_gemm<TileCfg<128, 128, 2, 4>, ALIGN_A, BKIND>(L, s);
   }
   return NF_EUNSUPPORTED;

@@ -50,19 +50,8 @@ nf_status launch_dma(GemmLaunch& L, hipStream_t s) {
 nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s) {
   switch (cfg) {
     case D256x256k32s4: return launch_dma<DmaCfg<256, 256, 32, 2, 4, 4>>(L, s);
-    case D128x256k32s5: return launch_dma<DmaCfg<128, 256, 32, 2, 4, 5>>(L, s);
-    case D128x128k64s3: return launch_dma<DmaCfg<128, 128, 64, 2, 2, 3>>(L, s);
     case D128x128k32s4: return launch_dma<DmaCfg<128, 128, 32, 2, 4, 4>>(L, s);
-    case D256x128k32s4: return launch_dma<DmaCfg<256, 128, 32, 4, 2, 4>>(L, s);
-    case D128x128k32s8: return launch_dma<DmaCfg<128, 128, 32, 2, 4, 8>>(L, s);
-    case D128x256k64s3: return launch_dma<DmaCfg<128, 256, 64, 2, 4, 3>>(L, s);
-    case D64x128k32s4w4: return launch_dma<DmaCfg<64, 128, 32, 1, 4, 4>>(L, s);
-    case D128x64k32s4w4: return launch_dma<DmaCfg<128, 64, 32, 4, 1, 4>>(L, s);
-    case D64x128k64s4w4: return launch_dma<DmaCfg<64, 128, 64, 1, 4, 4>>(L, s);
     case D128x128k64s3w8: return launch_dma<DmaCfg<128, 128, 64, 2, 4, 3>>(L, s);
-    case D128x192k32s4w4: return launch_dma<DmaCfg<128, 192, 32, 2, 2, 4>>(L, s);
-    case D128x192k32s3w4: return launch_dma<DmaCfg<128, 192, 32, 2, 2, 3>>(L, s);
-    case D128x192k64s3w8: return launch_dma<DmaCfg<128, 192, 64, 4, 2, 3>>(L, s);
   }
   return NF_EUNSUPPORTED;
 }

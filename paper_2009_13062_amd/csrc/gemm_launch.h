@@ -23,16 +23,15 @@ struct GemmLaunch {
   int nz1;
 };
 
-enum TileId { T128x128 = 0, T128x256, T256x128, T64x128, T64x64, T32x128, T256x256w8, T128x256w8, T128x128w8, kNumTiles };
-constexpr int kTileBM[kNumTiles] = {128, 128, 256, 64, 64, 32, 256, 128, 128};
-constexpr int kTileBN[kNumTiles] = {128, 256, 128, 128, 64, 128, 256, 256, 128};
+enum TileId { T128x128 = 0, T64x128, T64x64, T32x128, T128x128w8, kNumTiles };
+constexpr int kTileBM[kNumTiles] = {128, 64, 64, 32, 128};
+constexpr int kTileBN[kNumTiles] = {128, 128, 64, 128, 128};
 
 // Direct-to-LDS pipelined kernels for problems made of whole tiles (BM x BN, k-step, stages).
-enum DmaTileId { D256x256k32s4 = 0, D128x256k32s5, D128x128k64s3, D128x128k32s4, D256x128k32s4, D128x128k32s8,
-                 D128x256k64s3, D64x128k32s4w4, D128x64k32s4w4, D64x128k64s4w4, D128x128k64s3w8, D128x192k32s4w4, D128x192k32s3w4, D128x192k64s3w8, kNumDmaTiles };
-constexpr int kDmaBM[kNumDmaTiles] = {256, 128, 128, 128, 256, 128, 128, 64, 128, 64, 128, 128, 128, 128};
-constexpr int kDmaBN[kNumDmaTiles] = {256, 256, 128, 128, 128, 128, 256, 128, 64, 128, 128, 192, 192, 192};
-constexpr int kDmaBK[kNumDmaTiles] = {32, 32, 64, 32, 32, 32, 64, 32, 32, 64, 64, 32, 32, 64};
+enum DmaTileId { D256x256k32s4 = 0, D128x128k32s4, D128x128k64s3w8, kNumDmaTiles };
+constexpr int kDmaBM[kNumDmaTiles] = {256, 128, 128};
+constexpr int kDmaBN[kNumDmaTiles] = {256, 128, 128};
+constexpr int kDmaBK[kNumDmaTiles] = {32, 32, 64};
 // dense, 16-byte aligned A and B; NF_EUNSUPPORTED if the problem is not a whole number of tiles
 nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s);
 

@@ -47,9 +47,13 @@ __device__ __forceinline__ void lds_store16(lds_bf16_t* p, uint4 v) { *(lds_u32x
 __device__ __forceinline__ void lds_store8(lds_bf16_t* p, uint32_t a, uint32_t b) { *(lds_u32x2_t*)p = u32x2_t{a, b}; }
 
 constexpr int kBK = 64;             // k extent of one LDS stage
-constexpr int kPitchA = kBK + 8;    // A tile row pitch (elements): 144 B, 16-B slots rotate by one per row
-constexpr int kPadB = 16;           // B tile row pitch = BN + 16 elements: pitch mod 128 B = 32 B, so the 4
-                                    // rows touched by one transposing read fall into distinct bank groups
+// LDS has 64 banks (256 bytes per clock): a 16-byte read is served 16 lanes at a time, a transposing
+// 8-byte read 32 lanes at a time, and the lanes served together must fall into distinct banks.
+constexpr int kPitchA = kBK + 8;    // A tile row pitch (elements): 144 B = 9 x 16 B, so 16 consecutive rows
+                                    // start in 16 different 16-byte bank groups
+constexpr int kPadB = 32;           // B tile row pitch = BN + 32 elements: pitch mod 256 B = 64 B (BN a multiple
+                                    // of 128) or 192 B (BN = 64), so the 4 rows x 64 B touched by 32 lanes of a
+                                    // transposing read tile the 256 bytes exactly
 
 struct Epilogue {
   const float* row_bias;    // [z][i] or null      (convolution bias per output channel)

@@ -86,9 +86,9 @@ int pick_dma(int rows, int cols, int K, long long problems) {
   if (f == -1) return -1;
   auto fits = [&](int t) { return rows % kDmaBM[t] == 0 && cols % kDmaBN[t] == 0 && K % kDmaBK[t] == 0; };
   if (f >= 0) return fits(f) ? f : -1;
-  // measured on MI355X: 256x256 tiles win once there are >= 4 workgroups per CU, otherwise 128x128
-  // tiles with a 32-deep k-step, 8 waves and 4 stages (two workgroups per CU)
-  if (fits(D256x256k32s4) && problems * (rows / 256) * (cols / 256) >= 1024) return D256x256k32s4;
+  // measured on MI355X: 256x256 tiles (one workgroup per CU) win as soon as they occupy most of the 256 CUs,
+  // otherwise 128x128 tiles with a 32-deep k-step, 8 waves and 4 stages (two workgroups per CU)
+  if (fits(D256x256k32s4) && problems * (rows / 256) * (cols / 256) >= 160) return D256x256k32s4;
   // one row tile and a long K: 64-deep k-steps fetch whole 128-byte lines of the activation rows
   if (rows == 128 && K >= 2048 && fits(D128x128k64s3w8)) return D128x128k64s3w8;
   if (fits(D128x128k32s4)) return D128x128k32s4;
