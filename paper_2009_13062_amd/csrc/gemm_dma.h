@@ -13,7 +13,7 @@
 //     16-byte fragment read cover all 16 16-byte groups of the 64 banks.
 //   B tile [BK][BN] (column contiguous): chunk c of row k is stored at position c ^ 4 (k % 4), so the
 //     4 rows x 64 bytes touched by 32 neighbouring lanes of a transposing read (ds_read_b64_tr_b16)
-//     fall into distinct banks.
+//     fall into distinct banks (no permutation where the row pitch itself is 64 or 192 bytes modulo 256).
 // Waiting is explicit: a thread's loads retire in order, so "stage kt has landed" is
 // s_waitcnt vmcnt(loads issued after it); a workgroup barrier then publishes every thread's share
 // and, at the same time, proves that the stage read in the previous step is free to be refilled.
@@ -34,11 +34,14 @@ struct DmaCfg {
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
   static constexpr int kARow = BK * 2, kBRow = BN * 2;                 // bytes per LDS row
   static constexpr int kABytes = BM * kARow, kBBytes = BK * kBRow, kStageBytes = kABytes + kBBytes;
-  static constexpr int kAInstr = kABytes / 1024 / kNW, kBInstr = kBBytes / 1024 / kNW;
-  static_assert(kAInstr * 1024 * kNW == kABytes && kBInstr * 1024 * kNW == kBBytes, "tile must split evenly");
-  static constexpr int kLoadsPerStage = kAInstr + kBInstr;
-  static constexpr int kInFlight = (NS - 2) * kLoadsPerStage;          // loads allowed to stay pending
-  static_assert(kInFlight < 64, "vmcnt has 6 bits");
+  // A stage is kBlocks load instructions of 1 KB (A blocks first, then B), dealt to the wavefronts round
+  // robin: wave w issues blocks w, w + kNW, ...; when kNW does not divide kBlocks the first kRem waves
+  // issue one more than the others.
+  static constexpr int kABlocks = kABytes / 1024, kBBlocks = kBBytes / 1024, kBlocks = kABlocks + kBBlocks;
+  static_assert(kABlocks * 1024 == kABytes && kBBlocks * 1024 == kBBytes, "tiles are whole 1 KB blocks");
+  static constexpr int kMaxPer = (kBlocks + kNW - 1) / kNW, kRem = kBlocks % kNW;
+  static_assert(NS >= 3, "NS-1 stages are in flight while one is multiplied");
+  static_assert((NS - 2) * kMaxPer < 64, "vmcnt has 6 bits");
   static constexpr int kEpiPitch = BN + 4;
   static constexpr int kLdsEpi = WGM * 32 * kEpiPitch * (int)sizeof(float);
   static constexpr int kLdsPipe = NS * kStageBytes;
@@ -50,8 +53,12 @@ struct DmaCfg {
   // transposing 8-byte read 32 lanes at a time, and the lanes of one such group must cover distinct banks.
   static constexpr int kARowsPer256 = 256 / kARow;                      // A rows that share one bank span
   __device__ static __forceinline__ int swz_a(int row) { return (row / kARowsPer256) % kACpr; }
-  static_assert(kBCpr % 16 == 0, "B rows are permuted in units of 16 chunks");
-  static constexpr int kBSwz = 4;                                       // chunk ^= 4 (k % 4) stays in the row
+  // B rows whose pitch is 64 or 192 bytes modulo 256 (BN = 96, 288) need no permutation: four consecutive
+  // k rows already start 64 bytes apart in the banks.  Otherwise chunk ^= 4 (k % 4), which stays in the row
+  // when rows are whole groups of 16 chunks.
+  static constexpr bool kBNatural = kBRow % 256 == 64 || kBRow % 256 == 192;
+  static_assert(kBNatural || kBCpr % 16 == 0, "B rows are permuted in units of 16 chunks");
+  static constexpr int kBSwz = kBNatural ? 0 : 4;
 };
 
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0 and
@@ -75,32 +82,39 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
   const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
   const int half = lane / 32, l32 = lane % 32, l16 = lane % 16;
 
-  // ---- what this lane fetches: element offsets of its 16-byte chunks at k-step 0
-  long a_src[Cfg::kAInstr], b_src[Cfg::kBInstr];
+  // ---- what this lane fetches: the global address of its 16-byte chunk of each of its blocks, advanced
+  // by one k-step after every issue (stages are issued in order)
+  const bf16_t* src[Cfg::kMaxPer];
+  long inc[Cfg::kMaxPer];
 #pragma unroll
-  for (int t = 0; t < Cfg::kAInstr; ++t) {
-    const int row = (t * Cfg::kNW + wave) * Cfg::kARpi + lane / Cfg::kACpr;
-    const int c = (lane % Cfg::kACpr) ^ Cfg::swz_a(row);
-    a_src[t] = (long)row * lda + c * 8;
+  for (int t = 0; t < Cfg::kMaxPer; ++t) {
+    const int blk = t * Cfg::kNW + wave;
+    if (blk < Cfg::kABlocks) {
+      const int row = blk * Cfg::kARpi + lane / Cfg::kACpr;
+      const int c = (lane % Cfg::kACpr) ^ Cfg::swz_a(row);
+      src[t] = A + (long)row * lda + c * 8;
+      inc[t] = BK;
+    } else {
+      const int flat = (blk - Cfg::kABlocks) * 64 + lane;    // chunk index in the row-major [BK][BN] LDS tile
+      const int krow = flat / Cfg::kBCpr;
+      const int c = (flat % Cfg::kBCpr) ^ (Cfg::kBSwz * (krow % 4));
+      src[t] = B + (long)krow * ldb + c * 8;
+      inc[t] = (long)BK * ldb;
+    }
   }
-#pragma unroll
-  for (int t = 0; t < Cfg::kBInstr; ++t) {
-    const int flat = (t * Cfg::kNW + wave) * 64 + lane;      // chunk index in the row-major [BK][BN] LDS tile
-    const int krow = flat / Cfg::kBCpr;
-    const int c = (flat % Cfg::kBCpr) ^ (Cfg::kBSwz * (krow % 4));
-    b_src[t] = (long)krow * ldb + c * 8;
-  }
+  const bool extra = Cfg::kRem == 0 || wave < Cfg::kRem;     // this wave issues kMaxPer loads per stage (else one less)
   auto issue_stage = [&](int kt) {
     lds_u8_t* stage = smem + (kt % NS) * Cfg::kStageBytes;
-    const bf16_t* a = A + (long)kt * BK;
-    const bf16_t* b = B + (long)kt * BK * ldb;
 #pragma unroll
-    for (int t = 0; t < Cfg::kAInstr; ++t)
-      __builtin_amdgcn_global_load_lds((glb_u8_t*)(a + a_src[t]), stage + (t * Cfg::kNW + wave) * 1024, 16, 0, 0);
-#pragma unroll
-    for (int t = 0; t < Cfg::kBInstr; ++t)
-      __builtin_amdgcn_global_load_lds((glb_u8_t*)(b + b_src[t]), stage + Cfg::kABytes + (t * Cfg::kNW + wave) * 1024,
-                                       16, 0, 0);
+    for (int t = 0; t < Cfg::kMaxPer; ++t) {
+      if (t + 1 < Cfg::kMaxPer || extra)
+        __builtin_amdgcn_global_load_lds((glb_u8_t*)src[t], stage + (t * Cfg::kNW + wave) * 1024, 16, 0, 0);
+      src[t] += inc[t];
+    }
+  };
+  // stage kt has landed once at most the loads of the NS-2 younger stages are pending
+  auto wait_landed = [&]() {
+    if (extra) wait_vmcnt<(NS - 2) * Cfg::kMaxPer>(); else wait_vmcnt<(NS - 2) * (Cfg::kMaxPer - 1)>();
   };
 
   // ---- where this lane reads its fragments (byte offsets inside a stage, k-step part added later)
@@ -131,9 +145,8 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
     if (s < nk) issue_stage(s);
 
   for (int kt = 0; kt < nk; ++kt) {
-    // stage kt has landed once at most the loads of the NS-2 younger stages are pending; near the
-    // end fewer stages were issued, so wait for everything.
-    if (kt + NS - 2 < nk) wait_vmcnt<Cfg::kInFlight>(); else wait_vmcnt<0>();
+    // near the end fewer stages were issued, so wait for everything
+    if (kt + NS - 2 < nk) wait_landed(); else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     const lds_u8_t* stage = smem + (kt % NS) * Cfg::kStageBytes;
     // All fragments of the k-step are read BEFORE the next stage's loads are issued: LDS reads that a

@@ -86,13 +86,24 @@ int pick_dma(int rows, int cols, int K, long long problems) {
   if (f == -1) return -1;
   auto fits = [&](int t) { return rows % kDmaBM[t] == 0 && cols % kDmaBN[t] == 0 && K % kDmaBK[t] == 0; };
   if (f >= 0) return fits(f) ? f : -1;
-  // measured on MI355X: 256x256 tiles (one workgroup per CU) win as soon as they occupy most of the 256 CUs,
-  // otherwise 128x128 tiles with a 32-deep k-step, 8 waves and 4 stages (two workgroups per CU)
-  if (fits(D256x256k32s4) && problems * (rows / 256) * (cols / 256) >= 160) return D256x256k32s4;
-  // one row tile and a long K: 64-deep k-steps fetch whole 128-byte lines of the activation rows
-  if (rows == 128 && K >= 2048 && fits(D128x128k64s3w8)) return D128x128k64s3w8;
-  if (fits(D128x128k32s4)) return D128x128k32s4;
-  return -1;
+  // Measured on MI355X: these kernels are bound by what ONE compute unit can pull through its vector
+  // memory path (about 22 GB/s per CU at HBM latency, 3x that for L2 hits), not by the matrix pipe, so
+  // the cost of a configuration is the operand bytes the busiest CU has to load: its share of the tiles
+  // times (A tile + B tile).  Wide tiles re-read the activation rows less often; a tile count that is a
+  // whole multiple of the 256 CUs leaves none of them idle.
+  constexpr long long kCUs = 256;
+  int best = -1;
+  long long best_cost = 0;
+  for (int t = 0; t < kNumDmaTiles; ++t) {
+    if (!fits(t)) continue;
+    if (t == D128x128k64s3w8 && !(rows == 128 && (K >= 2048 || fits(D128x384k32s4)))) continue;   // long-K / narrow layers only
+    const long long tiles = problems * (rows / kDmaBM[t]) * (cols / kDmaBN[t]);
+    const long long per_cu = (tiles + kCUs - 1) / kCUs;
+    long long cost = per_cu * ((long long)kDmaBM[t] + kDmaBN[t]) * K;
+    if (kDmaBK[t] == 64) cost -= cost / 16;               // whole 128-byte lines of A per k-step: slightly cheaper than k32
+    if (best < 0 || cost < best_cost) { best = t; best_cost = cost; }
+  }
+  return best;
 }
 
 // Tile choice for the register-staged kernels.  With one k-step of prefetch these kernels are bound by
