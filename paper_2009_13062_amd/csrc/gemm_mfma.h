@@ -249,7 +249,7 @@ struct TileCfg {
 template <int ACT>
 __device__ __forceinline__ float act_const(float v) {
   if constexpr (ACT == NF_ACT_RELU) return v > 0.f ? v : (v != v ? v : 0.f);
-  else if constexpr (ACT == NF_ACT_GELU) return 0.5f * v * (1.f + fast_erf(v * 0.70710678118654752440f));
+  else if constexpr (ACT == NF_ACT_GELU) return gelu_erf(v);
   else return v;
 }
 
@@ -270,15 +270,26 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
   // per-column constants of this lane (4 consecutive columns per 8-column group), fetched once, all
   // loads in flight together
   float cb[FN][4][4];
+  if (ep.col_bias != nullptr && cols_left >= Cfg::kBN && ((uintptr_t)(ep.col_bias + col_vec_off) & 15) == 0) {
+    // whole tile, 16-byte aligned vector: one 16-byte load per 4 columns, no per-column predicate
 #pragma unroll
-  for (int j = 0; j < FN; ++j)
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int col = wn * Cfg::WN + j * 32 + q * 8 + half * 4 + e;
-        cb[j][q][e] = (ep.col_bias != nullptr && col < cols_left) ? ep.col_bias[col_vec_off + col] : 0.f;
+      for (int q = 0; q < 4; ++q) {
+        const float4 v = *reinterpret_cast<const float4*>(ep.col_bias + col_vec_off + wn * Cfg::WN + j * 32 + q * 8 + half * 4);
+        cb[j][q][0] = v.x; cb[j][q][1] = v.y; cb[j][q][2] = v.z; cb[j][q][3] = v.w;
       }
+  } else {
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int col = wn * Cfg::WN + j * 32 + q * 8 + half * 4 + e;
+          cb[j][q][e] = (ep.col_bias != nullptr && col < cols_left) ? ep.col_bias[col_vec_off + col] : 0.f;
+        }
+  }
 
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
