@@ -270,8 +270,9 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
   // per-column constants of this lane (4 consecutive columns per 8-column group), fetched once, all
   // loads in flight together
   float cb[FN][4][4];
-  if (ep.col_bias != nullptr && cols_left >= Cfg::kBN && ((uintptr_t)(ep.col_bias + col_vec_off) & 15) == 0) {
-    // whole tile, 16-byte aligned vector: one 16-byte load per 4 columns, no per-column predicate
+  if (FN >= 3 && ep.col_bias != nullptr && cols_left >= Cfg::kBN && ((uintptr_t)(ep.col_bias + col_vec_off) & 15) == 0) {
+    // wide wave tiles (where the scalar form costs 48+ predicated loads per lane; measured slower on narrow
+    // ones), whole tile, 16-byte aligned vector: one 16-byte load per 4 columns, no per-column predicate
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
