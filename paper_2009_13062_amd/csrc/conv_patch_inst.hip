@@ -33,13 +33,15 @@ static nf_status launch_one(ConvPatchArgs& a, int B, hipStream_t s) {
 // 3x3, dilation 1, cig % 16 == 0, patch width <= 64.  The caller has filled everything but the tiling.
 nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
   if (a.S > 1) return launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4>>(a, B, s);   // fused narrow groups: one 32-channel block
-  // the tallest row tile that still gives every CU two workgroups
   const long long per_row_tile = (long long)((a.HoWo + 127) / 128) * a.nG * B;
   auto tiles = [&](int bm) { return per_row_tile * ((a.cog + bm - 1) / bm); };
   // 32 channels per stage (half as many barriers) where the patch copy still fits 8 chunks per thread
   const bool deep = a.cig % 32 == 0 && a.cig >= 128 && 32LL * ((a.PS + a.PW - 1) / a.PW) * a.cpr <= 12 * 256;
-  if (a.cog > 64 && tiles(128) >= 512) return launch_one<ConvPatchCfg<128, 3, 3, 16, 2, 2>>(a, B, s);
-  if (a.cog > 32 && tiles(64) >= 512)
+  // measured on MI355X (M = 32 ResNet-50 layers): a taller row tile re-copies the input patch less often and
+  // reuses every gathered B fragment for more output channels, which pays as long as about 400 workgroups
+  // remain; stride-2 layers copy four times the patch per output and prefer 128 rows from 200 workgroups up
+  if (a.cog > 64 && tiles(128) >= (a.stride > 1 ? 200 : 512)) return launch_one<ConvPatchCfg<128, 3, 3, 16, 2, 2>>(a, B, s);
+  if (a.cog > 32 && tiles(64) >= 400)
     return deep ? launch_one<ConvPatchCfg<64, 3, 3, 32, 1, 4>>(a, B, s) : launch_one<ConvPatchCfg<64, 3, 3, 16, 1, 4>>(a, B, s);
   return deep ? launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4>>(a, B, s) : launch_one<ConvPatchCfg<32, 3, 3, 16, 1, 4>>(a, B, s);
 }

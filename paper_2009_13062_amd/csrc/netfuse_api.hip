@@ -244,8 +244,11 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     int al = common_align({w}, {Kdim});
     while (al > 2 && (Kdim % (al / 2)) != 0) al /= 2;
     const long long problems = (long long)M * g * B;
-    const int tile = pick_tile(cog, HoWo, problems);
     const bool pointwise = KH == 1 && KW == 1 && stride == 1 && pad == 0;
+    int tile = pick_tile(cog, HoWo, problems);
+    // gathered B operand (strided or k x k taps): its loads are the expensive part, so a few output
+    // positions are better served by tall tiles that gather them once per 128 output channels (measured)
+    if (!pointwise && forced_tile() < 0 && HoWo <= 64 && cog >= 256) tile = T128x128w8;
     if (pointwise) {
       // a 1x1 convolution is a matrix product over the channel dimension with the H*W positions as
       // columns (the converse of Section 3.1's remark that a matmul is a 1x1 convolution)
