@@ -1,7 +1,8 @@
-// Instantiation and launch of the patch-gather convolution kernels (3x3, bf16).
+// Instantiation and launch of the patch-gather convolution kernels (3x3 and the 7x7 stem, bf16).
 #include <atomic>
 
 #include "conv_patch.h"
+#include "conv_stem.h"
 #include "gemm_launch.h"
 
 namespace nf {
@@ -44,6 +45,22 @@ nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
   if (a.cog > 32 && tiles(64) >= 400)
     return deep ? launch_one<ConvPatchCfg<64, 3, 3, 32, 1, 4>>(a, B, s) : launch_one<ConvPatchCfg<64, 3, 3, 16, 1, 4>>(a, B, s);
   return deep ? launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4>>(a, B, s) : launch_one<ConvPatchCfg<32, 3, 3, 16, 1, 4>>(a, B, s);
+}
+
+// 7x7, stride 2, pad 3, 3 input channels per group.  The caller has filled everything but the tiling and
+// has checked W % 8 == 0, 16-byte aligned x, and the patch width.
+nf_status launch_conv_stem(ConvStemArgs& a, int B, hipStream_t s) {
+  typedef ConvStemCfg<3> Cfg;
+  a.tiles_m = (a.cog + Cfg::kBM - 1) / Cfg::kBM;
+  a.tiles_n = (a.HoWo + Cfg::kBN - 1) / Cfg::kBN;
+  const long long total = (long long)a.tiles_m * a.tiles_n * a.nG * B;
+  if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
+  if (a.PW % 8 != 0 || a.PS % 8 != 0 || a.PS % a.PW != 0) return NF_EUNSUPPORTED;
+  if (3LL * (a.PS / a.PW) * a.cpr > Cfg::kPatchTasksPerThread * 256) return NF_EUNSUPPORTED;
+  const int lds = Cfg::lds_bytes(a.PS);
+  if (lds > 64 * 1024) return NF_EUNSUPPORTED;
+  hipLaunchKernelGGL((conv_stem_kernel<Cfg, 3>), dim3((unsigned)total), dim3(256), lds, s, a);
+  return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
 }
 
 }  // namespace nf

@@ -11,6 +11,7 @@
 #include "../../include/netfuse.h"
 #include "attention_kernels.h"
 #include "conv_patch.h"
+#include "conv_stem.h"
 #include "gemm_launch.h"
 #include "gemm_mfma.h"
 #include "generic_kernels.h"
@@ -260,6 +261,24 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
       return launch_gemm_any(bkind, al, tile, L, s);
     }
     static const bool no_patch = getenv("NETFUSE_NO_PATCH") != nullptr;
+    if (!no_patch && KH == 7 && KW == 7 && stride == 2 && pad == 3 && dilation == 1 && cig == 3 && W % 8 == 0 &&
+        aligned(x, 16)) {
+      // the ResNet stem: a few input channels under a wide kernel (conv_stem.h)
+      const int PWs = (std::max(8 + W, 2 * ((int)Wo - 1) + 12) + 7) / 8 * 8;     // copied columns and gathered segments fit
+      const int span_s = (int)std::min<long long>(Ho, (126 + Wo) / Wo + 1);      // output rows one 128-position tile can touch
+      const int PHs = (span_s - 1) * 2 + 7;
+      ConvStemArgs c;
+      memset(&c, 0, sizeof(c));
+      c.x = (const bf16_t*)x; c.w = (const bf16_t*)w; c.R = (const bf16_t*)residual; c.y = (bf16_t*)y;
+      c.cog = cog; c.nG = M * g; c.H = H; c.W = W; c.Ho = (int)Ho; c.Wo = (int)Wo; c.HoWo = HoWo;
+      c.PW = PWs; c.PS = PHs * PWs; c.cpr = W / 8;
+      c.x_group = (long)cig * H * W; c.x_image = (long)Ctot_in * H * W;
+      c.y_group = (long)cog * HoWo; c.y_image = (long)Ctot_out * HoWo;
+      c.ep = a.ep;
+      c.ep.row_vec_stride0 = cog;
+      const nf_status st = launch_conv_stem(c, B, s);
+      if (st != NF_EUNSUPPORTED) return st;
+    }
     // patch geometry (conv_patch.h): image column ix sits at patch column ix + 8; rows are copied in
     // chunks of VW pixels; a 128-position tile touches at most `span` output rows
     const int VW = W % 8 == 0 ? 8 : (W % 4 == 0 ? 4 : (W % 2 == 0 ? 2 : 1));

@@ -152,6 +152,9 @@ CONV_CASES = [
     (3, 1, 64, 64, 8, 28, 28, 3, 3, 1, 1, 1),      # fused narrow groups: 8 channels per group, 4 groups per block
     (2, 2, 64, 64, 4, 16, 16, 3, 3, 2, 1, 1),      # fused narrow groups: 16 per group, stride 2, batch 2
     (1, 1, 32, 32, 8, 56, 56, 3, 3, 1, 1, 1),      # fused narrow groups: 4 per group on a 56x56 image
+    (3, 1, 3, 64, 1, 56, 56, 7, 7, 2, 3, 1),       # stem kernel: 28-wide output, tiles that start mid-row
+    (2, 2, 3, 96, 1, 24, 40, 7, 7, 2, 3, 1),       # stem kernel: batch 2, non-square image, a partial second row tile
+    (2, 1, 3, 64, 1, 30, 30, 7, 7, 2, 3, 1),       # stem shape whose rows are not whole 16-byte chunks (gathering loader)
 ]
 
 
