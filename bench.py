@@ -314,14 +314,15 @@ def cpu_baseline(name):
     threads = int(os.environ.get("OMP_NUM_THREADS", cores))
     oracle.build()
     if kind == "encoder":
-        ms = 4 if p["seq"] <= 128 else 1
-        shape = NI.EncoderShape(layers=1, seq=p["seq"])
+        # about 10 s including input generation: every model through 1 layer (seq 128), 4 models through 1 layer (seq 512)
+        ms, nl = (min(M, 32), 1) if p["seq"] <= 128 else (min(M, 4), 1)
+        shape = NI.EncoderShape(layers=nl, seq=p["seq"])
         inp = NI.encoder_stack(ms, shape, cfg=p["cfg"], bf16=True)
         t0 = time.perf_counter()
         OM.encoder_stack(inp, ms, 1, shape.seq, shape.heads, out_bf16=True)
         dt = time.perf_counter() - t0
-        per_inference = dt / ms * p["layers"]
-        sample = "%d of %d models x 1 of %d layers (seq %d), scaled by the layer count" % (ms, M, p["layers"], p["seq"])
+        per_inference = dt / ms / nl * p["layers"]
+        sample = "%d of %d models x %d of %d layers (seq %d), scaled by the layer count" % (ms, M, nl, p["layers"], p["seq"])
     else:
         spec = NI.resnet_spec(cardinality=p["card"], base_width=p["bw"])
         inp = NI.resnet_params(spec, 1, cfg=p["cfg"], bf16=True)
