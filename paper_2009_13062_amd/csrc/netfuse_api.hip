@@ -457,8 +457,14 @@ nf_status netfuse_maxpool2d(const void* x, void* y, int B, int Ctot, int H, int 
   if (n_in >= kMaxElems || n_out >= kMaxElems) return NF_EINVAL;
   const size_t esz = dt == NF_F32 ? 4 : 2;
   if (!aligned(x, esz) || !aligned(y, esz)) return NF_EINVAL;
-  const unsigned grid = grid_for(n_out, 256);
   hipStream_t s = (hipStream_t)stream;
+  if (dt == NF_BF16 && k == 3 && stride == 2 && pad == 1 && W % 8 == 0 && aligned(x, 16) && aligned(y, 8)) {
+    // Wo = W / 2 is a multiple of 4: four outputs per thread from 16-byte loads
+    hipLaunchKernelGGL(maxpool3x3s2_bf16_kernel, dim3(grid_for(n_out / 4, 256)), dim3(256), 0, s, (const bf16_t*)x,
+                       (bf16_t*)y, H, W, Ho, Wo, (size_t)(n_out / 4));
+    return launched();
+  }
+  const unsigned grid = grid_for(n_out, 256);
   if (dt == NF_F32)
     hipLaunchKernelGGL(maxpool2d_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x, (float*)y, H, W, Ho,
                        Wo, k, stride, pad, (size_t)n_out);

@@ -193,6 +193,48 @@ __global__ __launch_bounds__(256) void maxpool2d_kernel(const T* __restrict__ x,
   }
 }
 
+// The ResNet stem pool: 3x3 window, stride 2, pad 1 on bf16 rows whose width is a multiple of 8.  One
+// thread produces 4 consecutive outputs of a row from one 16-byte load (8 pixels) plus the pixel to their
+// left per input row; same comparison as the general kernel (v > best, so NaN inputs are ignored).
+__global__ __launch_bounds__(256) void maxpool3x3s2_bf16_kernel(const bf16_t* __restrict__ x, bf16_t* y, int H, int W,
+                                                                int Ho, int Wo, size_t total4) {
+  const int q = Wo / 4;
+  for (size_t o = (size_t)blockIdx.x * 256 + threadIdx.x; o < total4; o += (size_t)gridDim.x * 256) {
+    const int ox0 = (int)(o % q) * 4;
+    size_t t = o / q;
+    const int oy = (int)(t % Ho);
+    const size_t bc = t / Ho;
+    const bf16_t* xc = x + bc * (size_t)H * W;
+    float m[9];                                   // column maxima over the 3 input rows: cols 2 ox0 - 1 .. 2 ox0 + 7
+#pragma unroll
+    for (int c = 0; c < 9; ++c) m[c] = -INFINITY;
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky) {
+      const int iy = oy * 2 + ky - 1;
+      if (iy < 0 || iy >= H) continue;
+      const bf16_t* row = xc + (size_t)iy * W + ox0 * 2;
+      const uint4 v = *reinterpret_cast<const uint4*>(row);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      if (ox0 > 0) { const float l = bf16_to_f32(row[-1]); m[0] = l > m[0] ? l : m[0]; }
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const float f = __uint_as_float(c % 2 ? (w[c / 2] & 0xffff0000u) : (w[c / 2] << 16));
+        m[c + 1] = f > m[c + 1] ? f : m[c + 1];
+      }
+    }
+    uint32_t out[2];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float best = m[2 * j];
+      best = m[2 * j + 1] > best ? m[2 * j + 1] : best;
+      best = m[2 * j + 2] > best ? m[2 * j + 2] : best;
+      const uint32_t h = (uint32_t)f32_to_bf16(best);
+      if (j % 2) out[j / 2] |= h << 16; else out[j / 2] = h;
+    }
+    *reinterpret_cast<uint2*>(y + (bc * Ho + oy) * (size_t)Wo + ox0) = make_uint2(out[0], out[1]);
+  }
+}
+
 // Global average pooling: one wavefront per (b, channel).
 template <typename T>
 __global__ __launch_bounds__(256) void avgpool_global_kernel(const T* __restrict__ x, T* y, size_t nchan,

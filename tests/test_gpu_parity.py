@@ -197,6 +197,20 @@ def test_conv_reads_exactly_its_group(nf, oracle, dtype):
         assert np.array_equal(got, oracle.conv2d(x, w, M, g=g, pad=pad))
 
 
+def test_maxpool_stem_shape_bf16(nf, oracle):
+    """3x3 / stride 2 / pad 1 on rows of 8k pixels takes the four-outputs-per-thread kernel: exact, edges
+    (odd height, first and last columns), all-negative windows and NaN inputs included."""
+    dtype = torch.bfloat16
+    for (B, C, H, W) in ((1, 6, 16, 24), (2, 3, 15, 8), (1, 2, 112, 112)):
+        x = rnd(B, C, H, W)
+        x[0, 0] = -np.abs(x[0, 0]) - 1.0
+        x = grid(x, dtype)
+        x[0, 1, 3, 5] = np.nan
+        x[0, 1, 0, 0] = np.nan
+        got, ref = host(nf.maxpool2d(dev(x, dtype), 3, 2, 1)), oracle.maxpool2d(x, 3, 2, 1)
+        assert got.shape == ref.shape and np.array_equal(got, ref, equal_nan=True), (B, C, H, W)
+
+
 def test_linear_equals_pointwise_conv_on_gpu(nf):
     """Section 3.1: a matmul is a 1x1 convolution -- both entry points, same numbers."""
     M, N, K, Nout = 3, 64, 128, 96
