@@ -39,7 +39,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_mfma_kernel(GemmArgs a) {
       ATileLoader<Cfg::kBM, ALIGN_A, false, Cfg::kThreads> la;
       la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
       BDenseLoader<Cfg::kBN, BKIND == 0 ? 1 : BKIND, false, Cfg::kThreads> lb;
-      lb.base = Bbase + col0; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
+      lb.base = Bbase + col0; lb.end = a.B_end; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
       gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
     };
     if constexpr (ALIGN_A == 16 && BKIND == 8) {
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_mfma_kernel(GemmArgs a) {
         ATileLoader<Cfg::kBM, 16, true, Cfg::kThreads> la;
         la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
         BDenseLoader<Cfg::kBN, 8, true, Cfg::kThreads> lb;
-        lb.base = Bbase + col0; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
+        lb.base = Bbase + col0; lb.end = a.B_end; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
         gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
       } else {
         general();

@@ -11,6 +11,7 @@ namespace nf {
 
 struct GemmArgs {
   const bf16_t* A; const bf16_t* B; const bf16_t* R; bf16_t* C;
+  const bf16_t* B_end;                     // one past the last element of the B operand (loaders that read past a row)
   long lda, ldb, ldc;
   long sA0, sA1, sB0, sB1, sC0, sC1;      // strides of the two batch coordinates (elements)
   int rows, cols, K, nz0, tiles_m, tiles_n;

@@ -126,26 +126,34 @@ struct ATileLoader {
 
 // ------------------------------------------------------------------------------------------
 // B tile loader, dense k-major matrix B[k][j] (row pitch ldb): [64][BN] copied as is.
-// VEC = 8 / 4 / 1 elements per access (16 / 8 / 2-byte aligned rows; cols % VEC == 0).
+// VEC = 8 / 4 / 1: rows aligned to 16 / 8 / 2 bytes (cols % VEC == 0).
 // ------------------------------------------------------------------------------------------
 template <int BN, int VEC, bool FULL, int NT>
 struct BDenseLoader {
   static constexpr int kPitch = BN + kPadB;
-  static constexpr int kPerRow = BN / VEC;
+  // VEC = 1 (rows that start at any 2-byte address, e.g. 7x7 = 49 positions per channel) still moves 8
+  // elements per access: the global side is an unaligned 16-byte load, the LDS side is aligned.  The
+  // elements such a chunk reads past the last valid column belong to the next row; they only feed output
+  // columns that are never stored.  Only the chunk that would cross the END of the operand (`end`) is read
+  // element by element.
+  static constexpr int kW = VEC == 1 ? 8 : VEC;          // elements per task
+  static constexpr int kPerRow = BN / kW;
   static constexpr int kTasks = kBK * kPerRow;
   static constexpr int kPer = kTasks / NT;
   static_assert(kTasks % NT == 0, "tile too small for the workgroup");
-  static constexpr int kDw = VEC == 8 ? 4 : (VEC == 4 ? 2 : 1);
+  static constexpr int kDw = kW == 8 ? 4 : 2;
   const bf16_t* base;   // B + problem offset + col0
+  const bf16_t* end;    // one past the last element of the whole B operand (VEC = 1 only)
   long ldb;
   int cols_left, K;
   struct Regs { uint32_t v[kPer][kDw]; };
+  struct __attribute__((packed, aligned(2))) unaligned16 { uint4 v; };
 
   __device__ __forceinline__ void fetch(Regs& regs, int k0, int tid) const {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
       const int task = tid + t * NT;
-      const int k = k0 + task / kPerRow, j = (task % kPerRow) * VEC;
+      const int k = k0 + task / kPerRow, j = (task % kPerRow) * kW;
       const bf16_t* p = base + (long)k * ldb + j;
       const bool live = FULL || (k < K && j < cols_left);
       if constexpr (VEC == 8) {
@@ -155,7 +163,18 @@ struct BDenseLoader {
         const uint2 v = live ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
         regs.v[t][0] = v.x; regs.v[t][1] = v.y;
       } else {
-        regs.v[t][0] = live ? (uint32_t)*p : 0u;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (live) {
+          if (p + 8 <= end) {
+            v = reinterpret_cast<const unaligned16*>(p)->v;
+          } else {
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = p + e < end ? (uint32_t)p[e] : 0u;
+            v = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+          }
+        }
+        regs.v[t][0] = v.x; regs.v[t][1] = v.y; regs.v[t][2] = v.z; regs.v[t][3] = v.w;
       }
     }
   }
@@ -163,10 +182,9 @@ struct BDenseLoader {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
       const int task = tid + t * NT;
-      lds_bf16_t* dst = lds + (task / kPerRow) * kPitch + (task % kPerRow) * VEC;
-      if constexpr (VEC == 8) lds_store16(dst, make_uint4(regs.v[t][0], regs.v[t][1], regs.v[t][2], regs.v[t][3]));
-      else if constexpr (VEC == 4) lds_store8(dst, regs.v[t][0], regs.v[t][1]);
-      else *dst = (bf16_t)regs.v[t][0];
+      lds_bf16_t* dst = lds + (task / kPerRow) * kPitch + (task % kPerRow) * kW;
+      if constexpr (kW == 8) lds_store16(dst, make_uint4(regs.v[t][0], regs.v[t][1], regs.v[t][2], regs.v[t][3]));
+      else lds_store8(dst, regs.v[t][0], regs.v[t][1]);
     }
   }
 };

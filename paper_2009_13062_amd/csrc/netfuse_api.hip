@@ -117,7 +117,7 @@ int pick_tile(int rows, int cols, long long problems) {
     return problems * ((rows + kTileBM[t] - 1) / kTileBM[t]) * ((cols + kTileBN[t] - 1) / kTileBN[t]);
   };
   if (rows <= 32) return T32x128;
-  if (cols <= 64) return T64x64;
+  if (cols <= 64) return rows > 64 && tiles(T128x128w8) >= 512 ? T128x128w8 : T64x64;   // measured on 7x7 images
   if (rows > 64 && tiles(T128x128w8) >= 512) return T128x128w8;
   if (tiles(T64x128) >= 512) return T64x128;
   return T32x128;
@@ -173,6 +173,7 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     memset(&L, 0, sizeof(L));
     GemmArgs& a = L.a;
     a.A = (const bf16_t*)X; a.B = (const bf16_t*)W; a.R = (const bf16_t*)residual; a.C = (bf16_t*)Y;
+    a.B_end = a.B + (long long)M * K * Nout;
     a.lda = K; a.ldb = Nout; a.ldc = Nout;
     a.sA0 = (long)N * K; a.sB0 = (long)K * Nout; a.sC0 = (long)N * Nout;
     a.rows = N; a.cols = Nout; a.K = K; a.nz0 = M;
@@ -232,6 +233,7 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     memset(&L, 0, sizeof(L));
     GemmArgs& a = L.a;
     a.A = (const bf16_t*)w; a.B = (const bf16_t*)x; a.R = (const bf16_t*)residual; a.C = (bf16_t*)y;
+    a.B_end = a.B + (long long)B * Ctot_in * H * W;
     a.lda = Kdim; a.ldc = HoWo;
     a.sA0 = (long)cog * Kdim; a.sA1 = 0;
     a.sB0 = (long)cig * H * W; a.sB1 = (long)Ctot_in * H * W;
