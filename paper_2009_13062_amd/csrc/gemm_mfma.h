@@ -126,7 +126,7 @@ struct ATileLoader {
 
 // ------------------------------------------------------------------------------------------
 // B tile loader, dense k-major matrix B[k][j] (row pitch ldb): [64][BN] copied as is.
-// VEC = 8 / 4 / 1: rows aligned to 16 / 8 / 2 bytes (cols % VEC == 0).
+// VEC = 8: rows aligned to 16 bytes and cols % 8 == 0; VEC = 1: any rows.
 // ------------------------------------------------------------------------------------------
 template <int BN, int VEC, bool FULL, int NT>
 struct BDenseLoader {
@@ -136,12 +136,13 @@ struct BDenseLoader {
   // elements such a chunk reads past the last valid column belong to the next row; they only feed output
   // columns that are never stored.  Only the chunk that would cross the END of the operand (`end`) is read
   // element by element.
-  static constexpr int kW = VEC == 1 ? 8 : VEC;          // elements per task
+  static_assert(VEC == 8 || VEC == 1, "16-byte aligned rows or any rows");
+  static constexpr int kW = 8;                           // elements per task
   static constexpr int kPerRow = BN / kW;
   static constexpr int kTasks = kBK * kPerRow;
   static constexpr int kPer = kTasks / NT;
   static_assert(kTasks % NT == 0, "tile too small for the workgroup");
-  static constexpr int kDw = kW == 8 ? 4 : 2;
+  static constexpr int kDw = 4;
   const bf16_t* base;   // B + problem offset + col0
   const bf16_t* end;    // one past the last element of the whole B operand (VEC = 1 only)
   long ldb;
@@ -159,9 +160,6 @@ struct BDenseLoader {
       if constexpr (VEC == 8) {
         const uint4 v = live ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
         regs.v[t][0] = v.x; regs.v[t][1] = v.y; regs.v[t][2] = v.z; regs.v[t][3] = v.w;
-      } else if constexpr (VEC == 4) {
-        const uint2 v = live ? *reinterpret_cast<const uint2*>(p) : make_uint2(0, 0);
-        regs.v[t][0] = v.x; regs.v[t][1] = v.y;
       } else {
         uint4 v = make_uint4(0, 0, 0, 0);
         if (live) {
@@ -183,8 +181,7 @@ struct BDenseLoader {
     for (int t = 0; t < kPer; ++t) {
       const int task = tid + t * NT;
       lds_bf16_t* dst = lds + (task / kPerRow) * kPitch + (task % kPerRow) * kW;
-      if constexpr (kW == 8) lds_store16(dst, make_uint4(regs.v[t][0], regs.v[t][1], regs.v[t][2], regs.v[t][3]));
-      else lds_store8(dst, regs.v[t][0], regs.v[t][1]);
+      lds_store16(dst, make_uint4(regs.v[t][0], regs.v[t][1], regs.v[t][2], regs.v[t][3]));
     }
   }
 };

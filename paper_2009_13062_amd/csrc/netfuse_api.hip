@@ -51,7 +51,6 @@ inline unsigned grid_for(long long total, int per_block, long long cap = 1 << 20
 nf_status launch_gemm_any(int bkind, int align_a, int tile, GemmLaunch& L, hipStream_t s) {
   switch (bkind) {
     case 8: return launch_gemm_bkind<8>(align_a, tile, L, s);
-    case 4: return launch_gemm_bkind<4>(align_a, tile, L, s);
     case 1: return launch_gemm_bkind<1>(align_a, tile, L, s);
     case 0: return launch_gemm_bkind<0>(align_a, tile, L, s);
   }
@@ -166,7 +165,6 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     // vector width of the B loader: its chunks must not straddle the end of a row
     int bkind = 1;
     if (al_b == 16 && Nout % 8 == 0) bkind = 8;
-    else if (al_b >= 8 && Nout % 4 == 0) bkind = 4;
     int al = al_a;
     while (al > 2 && (K % (al / 2)) != 0) al /= 2;
     GemmLaunch L;
@@ -259,7 +257,6 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
       const int al_b = common_align({x}, {(long long)H * W});
       int bkind = 1;
       if (al_b == 16 && HoWo % 8 == 0) bkind = 8;
-      else if (al_b >= 8 && HoWo % 4 == 0) bkind = 4;
       return launch_gemm_any(bkind, al, tile, L, s);
     }
     static const bool no_patch = getenv("NETFUSE_NO_PATCH") != nullptr;
