@@ -46,6 +46,7 @@ struct DmaCfg {
   static constexpr int kLdsEpi = WGM * 32 * kEpiPitch * (int)sizeof(float);
   static constexpr int kLdsPipe = NS * kStageBytes;
   static constexpr int kLdsBytes = kLdsPipe > kLdsEpi ? kLdsPipe : kLdsEpi;
+  static_assert(kLdsBytes <= 160 * 1024, "pipeline stages and epilogue staging must fit the 160 KB of LDS");
   static constexpr int kACpr = BK / 8, kARpi = 64 / kACpr;              // A: chunks per row, rows per instruction
   static constexpr int kBCpr = BN / 8;                                  // B: chunks per row (rows need not divide 64)
   static_assert(BN % 32 == 0, "whole 32-column MFMA blocks");
