@@ -52,7 +52,7 @@ nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s) {
     case D256x256k32s4: return launch_dma<DmaCfg<256, 256, 32, 2, 4, 4>>(L, s);
     case D128x128k32s4: return launch_dma<DmaCfg<128, 128, 32, 2, 4, 4>>(L, s);
     case D128x128k64s3w8: return launch_dma<DmaCfg<128, 128, 64, 2, 4, 3>>(L, s);
-    case D128x384k32s4: return launch_dma<DmaCfg<128, 384, 32, 2, 4, 4>>(L, s);
+    case D128x384k32s4w12: return launch_dma<DmaCfg<128, 384, 32, 2, 6, 4>>(L, s);
     case D128x288k32s4w12: return launch_dma<DmaCfg<128, 288, 32, 4, 3, 4>>(L, s);
     case D128x96k64s4w12: return launch_dma<DmaCfg<128, 96, 64, 4, 3, 4>>(L, s);
   }

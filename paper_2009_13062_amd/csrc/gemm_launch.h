@@ -29,7 +29,7 @@ constexpr int kTileBM[kNumTiles] = {128, 64, 64, 32, 128};
 constexpr int kTileBN[kNumTiles] = {128, 128, 64, 128, 128};
 
 // Direct-to-LDS pipelined kernels for problems made of whole tiles (BM x BN, k-step, stages).
-enum DmaTileId { D256x256k32s4 = 0, D128x128k32s4, D128x128k64s3w8, D128x384k32s4, D128x288k32s4w12, D128x96k64s4w12, kNumDmaTiles };
+enum DmaTileId { D256x256k32s4 = 0, D128x128k32s4, D128x128k64s3w8, D128x384k32s4w12, D128x288k32s4w12, D128x96k64s4w12, kNumDmaTiles };
 constexpr int kDmaBM[kNumDmaTiles] = {256, 128, 128, 128, 128, 128};
 constexpr int kDmaBN[kNumDmaTiles] = {256, 128, 128, 384, 288, 96};
 constexpr int kDmaBK[kNumDmaTiles] = {32, 32, 64, 32, 32, 64};

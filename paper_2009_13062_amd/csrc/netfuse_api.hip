@@ -96,7 +96,7 @@ int pick_dma(int rows, int cols, int K, long long problems) {
   long long best_cost = 0;
   for (int t = 0; t < kNumDmaTiles; ++t) {
     if (!fits(t)) continue;
-    if (t == D128x128k64s3w8 && !(rows == 128 && (K >= 2048 || fits(D128x384k32s4)))) continue;   // long-K / narrow layers only
+    if (t == D128x128k64s3w8 && !(rows == 128 && (K >= 2048 || fits(D128x384k32s4w12)))) continue;   // long-K / narrow layers only
     const long long tiles = problems * (rows / kDmaBM[t]) * (cols / kDmaBN[t]);
     const long long per_cu = (tiles + kCUs - 1) / kCUs;
     long long cost = per_cu * ((long long)kDmaBM[t] + kDmaBN[t]) * K;
