@@ -188,6 +188,9 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
           s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][sb], qf[kk], s_acc[sb], 0, 0, 0);
     }
     // register r of block sb is key j0 + 32 sb + 8 (r/4) + 4 half + r%4, query lane%32
+    // Without a mask and with a positive scale (uniform over the launch) the scores stay unscaled: the running
+    // maximum is taken on them and scaled once, and scale and maximum enter the exponent in one fma.
+    const bool raw = mk == nullptr && sc > 0.f;
     if (mk != nullptr) {                       // uniform branch: additive key mask (in log2 units)
       float mv[2][16];
 #pragma unroll
@@ -201,7 +204,7 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) s_acc[sb][r] = fmaf(s_acc[sb][r], sc, mv[sb][r] * kLog2e);
-    } else {
+    } else if (!raw) {
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -213,7 +216,7 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = j0 + sb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-          s_acc[sb][r] = key < a.S ? s_acc[sb][r] : -3.0e38f;
+          s_acc[sb][r] = key < a.S ? s_acc[sb][r] : -3.0e38f;      // stays the minimum under a positive scale
         }
     }
     float mloc = -3.0e38f;
@@ -222,11 +225,13 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
 #pragma unroll
       for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s_acc[sb][r]);
     mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
+    if (raw) mloc = fmaxf(mloc * sc, -3.0e38f);
     const float mnew = fmaxf(mrun, mloc);
     const float corr = __builtin_amdgcn_exp2f(mrun - mnew);
     mrun = mnew;
     float psum = 0.f;
     bf16x8_t pf[2][2];                         // [sb][16-key step]
+    const float esc = raw ? sc : 1.0f;         // exponent = s * esc - mnew
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -234,10 +239,10 @@ __global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int
         uint32_t w[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const float p0 = __builtin_amdgcn_exp2f(s_acc[sb][8 * st + 2 * e] - mnew);
-          const float p1 = __builtin_amdgcn_exp2f(s_acc[sb][8 * st + 2 * e + 1] - mnew);
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[sb][8 * st + 2 * e], esc, -mnew));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[sb][8 * st + 2 * e + 1], esc, -mnew));
           w[e] = pack_bf16x2(p0, p1);
-          psum += __uint_as_float(w[e] << 16) + __uint_as_float(w[e] & 0xffff0000u);   // sum what is multiplied
+          psum += p0 + p1;                     // fp32 sum of the unrounded weights
         }
         uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
         pf[sb][st] = __builtin_bit_cast(bf16x8_t, v);
