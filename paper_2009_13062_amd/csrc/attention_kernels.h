@@ -98,7 +98,7 @@ constexpr int kAttnKPitch = kAttnD + 8;     // K tile [key][t]: 144 B rows, 16-b
 constexpr int kAttnVPitch = kAttnD + 32;    // V tile [key][t]: 192 B rows, so the 4 keys x 64 B that 32 lanes of a
                                             // transposing read touch tile the 256 bytes of the 64 LDS banks
 
-__global__ __launch_bounds__(256) void attention_mfma_d64_kernel(AttnArgs a, int qblocks) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void attention_mfma_d64_kernel(AttnArgs a, int qblocks) {
   __shared__ __align__(16) bf16_t Ks_raw[2 * kAttnKB * kAttnKPitch];
   __shared__ __align__(16) bf16_t Vs_raw[2 * kAttnKB * kAttnVPitch];
   lds_bf16_t* const Ks = (lds_bf16_t*)Ks_raw;
