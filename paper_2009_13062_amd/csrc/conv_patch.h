@@ -24,6 +24,8 @@
 // One workgroup = one (image, group, 128-position tile, BM output channels).  Accumulators and the
 // fused epilogue (folded batch norm scale/shift, residual, ReLU) are those of gemm_mfma.h.
 #pragma once
+#include <type_traits>
+
 #include "gemm_mfma.h"
 
 namespace nf {
@@ -43,7 +45,8 @@ struct ConvPatchArgs {
   Epilogue ep;
 };
 
-template <int BM, int KH, int KW, int CB, int WGM, int WGN>
+// MINW: wavefronts per SIMD the register allocation must allow (workgroups per CU, at 4 waves each)
+template <int BM, int KH, int KW, int CB, int WGM, int WGN, int MINW = 1>
 struct ConvPatchCfg {
   static_assert(WGM * WGN == 4, "4 wavefronts");
   static constexpr int kBM = BM, kBN = 128, kWGM = WGM, kWGN = WGN, kThreads = 256;
@@ -60,6 +63,7 @@ struct ConvPatchCfg {
   static constexpr int kEpiPitch = kBN + 4;
   static constexpr int kLdsEpi = WGM * 32 * kEpiPitch * (int)sizeof(float);
   static constexpr int kPatchTasksMax = 12 * 256;
+  static constexpr int kMinWaves = MINW;
   // Extra elements before the upper half of a block's planes, chosen so that the two lane halves of a
   // gather read addresses 128 bytes apart modulo the 256 bytes of the 64 LDS banks (plane pitches are
   // multiples of 8 elements, so CB/2 planes are a multiple of 128 bytes).
@@ -71,8 +75,10 @@ struct ConvPatchCfg {
   }
 };
 
-template <class Cfg>
-__global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
+// VW: pixels per patch chunk (= a.VW), a compile-time constant so that the copy has no branches and stages a
+// chunk in 16, 8 or 4 bytes of registers.
+template <class Cfg, int VW>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWaves))) void conv_patch_kernel(ConvPatchArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   lds_bf16_t* As = (lds_bf16_t*)smem_raw;
   lds_bf16_t* Ps = As + Cfg::kBM * Cfg::kAPitch;
@@ -131,8 +137,8 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
       const int ci = row / PH, py = row - ci * PH;
       const int iy = iy0 + py;
       const bool live = task < ntasks && iy >= 0 && iy < a.H;
-      g_off[u] = live ? (ci * a.H + iy) * a.W + ch * a.VW : -1;
-      l_off[u] = ci * a.PS + (ci >= CB / 2 ? hshift : 0) + py * a.PW + kLPad + ch * a.VW;
+      g_off[u] = live ? (ci * a.H + iy) * a.W + ch * VW : -1;
+      l_off[u] = ci * a.PS + (ci >= CB / 2 ? hshift : 0) + py * a.PW + kLPad + ch * VW;
     }
   }
   // zero the whole patch once: padding and out-of-image rows are never written again
@@ -141,7 +147,8 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
   // ---- software pipeline over channel blocks: the global loads of block s+1 are in flight in
   // registers while block s is multiplied out of LDS
   uint4 va[kAPer];
-  uint4 pv[kNT];
+  typedef typename std::conditional<VW == 8, uint4, typename std::conditional<VW == 4, uint2, uint32_t>::type>::type patch_regs_t;
+  patch_regs_t pv[kNT];
   auto prefetch = [&](int ci0) {
 #pragma unroll
     for (int t = 0; t < kAPer; ++t) {
@@ -153,13 +160,13 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
     const bf16_t* xc = xg + (long)ci0 * a.H * a.W;
 #pragma unroll
     for (int u = 0; u < kNT; ++u) {
-      pv[u] = make_uint4(0, 0, 0, 0);
+      pv[u] = patch_regs_t{};
       if (g_off[u] >= 0) {
         const bf16_t* p = xc + g_off[u];
-        if (a.VW == 8) pv[u] = *reinterpret_cast<const uint4*>(p);
-        else if (a.VW == 4) { const uint2 t2 = *reinterpret_cast<const uint2*>(p); pv[u].x = t2.x; pv[u].y = t2.y; }
-        else if (a.VW == 2) pv[u].x = *reinterpret_cast<const uint32_t*>(p);
-        else pv[u].x = *p;
+        if constexpr (VW == 8) pv[u] = *reinterpret_cast<const uint4*>(p);
+        else if constexpr (VW == 4) pv[u] = *reinterpret_cast<const uint2*>(p);
+        else if constexpr (VW == 2) pv[u] = *reinterpret_cast<const uint32_t*>(p);
+        else pv[u] = *p;
       }
     }
   };
@@ -192,10 +199,10 @@ __global__ __launch_bounds__(256) void conv_patch_kernel(ConvPatchArgs a) {
     for (int u = 0; u < kNT; ++u) {
       if (g_off[u] >= 0) {
         lds_bf16_t* d = Ps + l_off[u];
-        if (a.VW == 8) lds_store16(d, pv[u]);
-        else if (a.VW == 4) lds_store8(d, pv[u].x, pv[u].y);
-        else if (a.VW == 2) *(__attribute__((address_space(3))) uint32_t*)d = pv[u].x;
-        else *d = (bf16_t)pv[u].x;
+        if constexpr (VW == 8) lds_store16(d, pv[u]);
+        else if constexpr (VW == 4) lds_store8(d, pv[u].x, pv[u].y);
+        else if constexpr (VW == 2) *(__attribute__((address_space(3))) uint32_t*)d = pv[u];
+        else *d = (bf16_t)pv[u];
       }
     }
     __syncthreads();

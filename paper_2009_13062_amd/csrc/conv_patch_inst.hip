@@ -7,6 +7,22 @@
 
 namespace nf {
 
+template <class Cfg, int VW>
+static nf_status launch_kernel(long long total, int lds, const ConvPatchArgs& a, hipStream_t s) {
+  auto kern = conv_patch_kernel<Cfg, VW>;
+  if (lds > 64 * 1024) {
+    static std::atomic<bool> opted_in{false};        // per kernel: idempotent, a benign race
+    if (!opted_in.load(std::memory_order_acquire)) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              160 * 1024) != hipSuccess)
+        return NF_ELAUNCH;
+      opted_in.store(true, std::memory_order_release);
+    }
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(256), lds, s, a);
+  return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
+}
+
 template <class Cfg>
 static nf_status launch_one(ConvPatchArgs& a, int B, hipStream_t s) {
   a.tiles_m = (a.cog + Cfg::kBM - 1) / Cfg::kBM;
@@ -17,23 +33,20 @@ static nf_status launch_one(ConvPatchArgs& a, int B, hipStream_t s) {
   if ((long long)Cfg::kCB * (a.PS / a.PW) * a.cpr > Cfg::kPatchTasksMax) return NF_EUNSUPPORTED;
   const int lds = Cfg::lds_bytes(a.PS);
   if (lds > 160 * 1024) return NF_EUNSUPPORTED;
-  auto kern = conv_patch_kernel<Cfg>;
-  if (lds > 64 * 1024) {
-    static std::atomic<int> opted_in{0};
-    if (opted_in.load(std::memory_order_acquire) < lds) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              160 * 1024) != hipSuccess)
-        return NF_ELAUNCH;
-      opted_in.store(160 * 1024, std::memory_order_release);
-    }
+  switch (a.VW) {
+    case 8: return launch_kernel<Cfg, 8>(total, lds, a, s);
+    case 4: return launch_kernel<Cfg, 4>(total, lds, a, s);
+    case 2: return launch_kernel<Cfg, 2>(total, lds, a, s);
+    case 1: return launch_kernel<Cfg, 1>(total, lds, a, s);
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(256), lds, s, a);
-  return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
+  return NF_EUNSUPPORTED;
 }
 
 // 3x3, dilation 1, cig % 16 == 0, patch width <= 64.  The caller has filled everything but the tiling.
 nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
-  if (a.S > 1) return launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4>>(a, B, s);   // fused narrow groups: one 32-channel block
+  // register budgets (last parameter) from measurements: three workgroups per CU pay for the 16-channel stages
+  // and for the single-stage fused kernel, not for 32-channel stages looping over many blocks
+  if (a.S > 1) return launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4, 3>>(a, B, s);   // fused narrow groups: one 32-channel block
   const long long per_row_tile = (long long)((a.HoWo + 127) / 128) * a.nG * B;
   auto tiles = [&](int bm) { return per_row_tile * ((a.cog + bm - 1) / bm); };
   // 32 channels per stage (half as many barriers) where the patch copy still fits 8 chunks per thread
@@ -43,8 +56,8 @@ nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
   // remain; stride-2 layers copy four times the patch per output and prefer 128 rows from 200 workgroups up
   if (a.cog > 64 && tiles(128) >= (a.stride > 1 ? 200 : 512)) return launch_one<ConvPatchCfg<128, 3, 3, 16, 2, 2>>(a, B, s);
   if (a.cog > 32 && tiles(64) >= 400)
-    return deep ? launch_one<ConvPatchCfg<64, 3, 3, 32, 1, 4>>(a, B, s) : launch_one<ConvPatchCfg<64, 3, 3, 16, 1, 4>>(a, B, s);
-  return deep ? launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4>>(a, B, s) : launch_one<ConvPatchCfg<32, 3, 3, 16, 1, 4>>(a, B, s);
+    return deep ? launch_one<ConvPatchCfg<64, 3, 3, 32, 1, 4, 2>>(a, B, s) : launch_one<ConvPatchCfg<64, 3, 3, 16, 1, 4, 2>>(a, B, s);
+  return deep ? launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4, 2>>(a, B, s) : launch_one<ConvPatchCfg<32, 3, 3, 16, 1, 4, 3>>(a, B, s);
 }
 
 // 7x7, stride 2, pad 3, 3 input channels per group.  The caller has filled everything but the tiling and
