@@ -77,7 +77,8 @@ struct ConvPatchCfg {
 
 // VW: pixels per patch chunk (= a.VW), a compile-time constant so that the copy has no branches and stages a
 // chunk in 16, 8 or 4 bytes of registers.
-template <class Cfg, int VW>
+// FUSED: S > 1 narrow groups share the block (block-diagonal weight tile filled once, single channel block).
+template <class Cfg, int VW, bool FUSED>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWaves))) void conv_patch_kernel(ConvPatchArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   lds_bf16_t* As = (lds_bf16_t*)smem_raw;
@@ -154,7 +155,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
     for (int t = 0; t < kAPer; ++t) {
       const int c = tid + t * 256, r = c / kCpr, ch = c - r * kCpr;
       va[t] = make_uint4(0, 0, 0, 0);
-      if (a.S == 1 && (kAChunks % 256 == 0 || c < kAChunks) && r < rows_left)
+      if (!FUSED && (kAChunks % 256 == 0 || c < kAChunks) && r < rows_left)
         va[t] = *reinterpret_cast<const uint4*>(wg + ((long)r * a.cig + ci0) * KHW + ch * 8);
     }
     const bf16_t* xc = xg + (long)ci0 * a.H * a.W;
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
     }
   };
   prefetch(0);
-  if (a.S > 1) {
+  if constexpr (FUSED) {
     // block-diagonal weight tile of S fused groups (single channel block): zero it, then drop each
     // row's cig_real*KHW weights (8-byte chunks) at its group's column offset
     for (int c = tid; c < Cfg::kBM * Cfg::kAPitch / 8; c += 256) lds_store16(As + c * 8, make_uint4(0, 0, 0, 0));
@@ -188,7 +189,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
 
   for (int ci0 = 0; ci0 < a.cig; ci0 += CB) {
     // ---- commit the prefetched block to LDS
-    if (a.S == 1) {
+    if constexpr (!FUSED) {
 #pragma unroll
       for (int t = 0; t < kAPer; ++t) {
         const int c = tid + t * 256, r = c / kCpr, ch = c - r * kCpr;

@@ -7,9 +7,9 @@
 
 namespace nf {
 
-template <class Cfg, int VW>
+template <class Cfg, int VW, bool FUSED>
 static nf_status launch_kernel(long long total, int lds, const ConvPatchArgs& a, hipStream_t s) {
-  auto kern = conv_patch_kernel<Cfg, VW>;
+  auto kern = conv_patch_kernel<Cfg, VW, FUSED>;
   if (lds > 64 * 1024) {
     static std::atomic<bool> opted_in{false};        // per kernel: idempotent, a benign race
     if (!opted_in.load(std::memory_order_acquire)) {
@@ -23,7 +23,7 @@ static nf_status launch_kernel(long long total, int lds, const ConvPatchArgs& a,
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
 }
 
-template <class Cfg>
+template <class Cfg, bool FUSED = false>
 static nf_status launch_one(ConvPatchArgs& a, int B, hipStream_t s) {
   a.tiles_m = (a.cog + Cfg::kBM - 1) / Cfg::kBM;
   a.tiles_n = (a.HoWo + Cfg::kBN - 1) / Cfg::kBN;
@@ -34,10 +34,10 @@ static nf_status launch_one(ConvPatchArgs& a, int B, hipStream_t s) {
   const int lds = Cfg::lds_bytes(a.PS);
   if (lds > 160 * 1024) return NF_EUNSUPPORTED;
   switch (a.VW) {
-    case 8: return launch_kernel<Cfg, 8>(total, lds, a, s);
-    case 4: return launch_kernel<Cfg, 4>(total, lds, a, s);
-    case 2: return launch_kernel<Cfg, 2>(total, lds, a, s);
-    case 1: return launch_kernel<Cfg, 1>(total, lds, a, s);
+    case 8: return launch_kernel<Cfg, 8, FUSED>(total, lds, a, s);
+    case 4: return launch_kernel<Cfg, 4, FUSED>(total, lds, a, s);
+    case 2: return launch_kernel<Cfg, 2, FUSED>(total, lds, a, s);
+    case 1: return launch_kernel<Cfg, 1, FUSED>(total, lds, a, s);
   }
   return NF_EUNSUPPORTED;
 }
@@ -46,7 +46,7 @@ static nf_status launch_one(ConvPatchArgs& a, int B, hipStream_t s) {
 nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
   // register budgets (last parameter) from measurements: three workgroups per CU pay for the 16-channel stages
   // and for the single-stage fused kernel, not for 32-channel stages looping over many blocks
-  if (a.S > 1) return launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4, 3>>(a, B, s);   // fused narrow groups: one 32-channel block
+  if (a.S > 1) return launch_one<ConvPatchCfg<32, 3, 3, 32, 1, 4, 3>, true>(a, B, s);   // fused narrow groups: one 32-channel block
   const long long per_row_tile = (long long)((a.HoWo + 127) / 128) * a.nG * B;
   auto tiles = [&](int bm) { return per_row_tile * ((a.cog + bm - 1) / bm); };
   // 32 channels per stage (half as many barriers) where the patch copy still fits 8 chunks per thread
