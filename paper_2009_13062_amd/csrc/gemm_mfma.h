@@ -241,6 +241,54 @@ struct BIm2colLoader {
   }
 };
 
+// B tile loader of a strided pointwise convolution (1x1 kernel, no padding: the projection shortcuts):
+// element (k, p) = x[k][(p / Wo) * stride][(p % Wo) * stride], always inside the image.  Task = one k row x
+// 8 consecutive output positions; one division per task, no bounds checks on the image.
+template <int BN, int NT>
+struct BStridedPointwiseLoader {
+  static constexpr int kPitch = BN + kPadB;
+  static constexpr int kPerRow = BN / 8;
+  static constexpr int kTasks = kBK * kPerRow;
+  static constexpr int kPer = kTasks / NT;
+  static_assert(kTasks % NT == 0, "tile too small for the workgroup");
+  const bf16_t* xg;     // first input plane of this group and image
+  Im2colGeom g;
+  int cols_left, K, col0;
+  struct Regs { uint4 v[kPer]; };
+
+  __device__ __forceinline__ void fetch(Regs& regs, int k0, int tid) const {
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int task = tid + t * NT;
+      const int k = k0 + task / kPerRow, j = (task % kPerRow) * 8;
+      uint32_t h[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) h[e] = 0u;
+      if (k < K && j < cols_left) {
+        const bf16_t* plane = xg + (long)k * g.H * g.W;
+        const int p = col0 + j;
+        int oy = p / g.Wo, ox = p - oy * g.Wo;
+        int off = (oy * g.W + ox) * g.stride;
+        const int row_step = (g.W - g.Wo) * g.stride;      // from the end of one output row to the start of the next
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (j + e < cols_left) h[e] = (uint32_t)plane[off];
+          off += g.stride;
+          if (++ox == g.Wo) { ox = 0; off += row_step; }
+        }
+      }
+      regs.v[t] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+    }
+  }
+  __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int task = tid + t * NT;
+      lds_store16(lds + (task / kPerRow) * kPitch + (task % kPerRow) * 8, regs.v[t]);
+    }
+  }
+};
+
 // ------------------------------------------------------------------------------------------
 // The tile main loop and epilogue
 // ------------------------------------------------------------------------------------------

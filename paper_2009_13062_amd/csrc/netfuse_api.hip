@@ -51,6 +51,7 @@ inline unsigned grid_for(long long total, int per_block, long long cap = 1 << 20
 nf_status launch_gemm_any(int bkind, int align_a, int tile, GemmLaunch& L, hipStream_t s) {
   switch (bkind) {
     case 8: return launch_gemm_bkind<8>(align_a, tile, L, s);
+    case 2: return launch_gemm_bkind<2>(align_a, tile, L, s);
     case 1: return launch_gemm_bkind<1>(align_a, tile, L, s);
     case 0: return launch_gemm_bkind<0>(align_a, tile, L, s);
   }
@@ -313,7 +314,7 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     }
     a.geom.H = H; a.geom.W = W; a.geom.KH = KH; a.geom.KW = KW; a.geom.Wo = (int)Wo;
     a.geom.stride = stride; a.geom.pad = pad; a.geom.dil = dilation;
-    return launch_gemm_any(0, al, tile, L, s);
+    return launch_gemm_any(KH == 1 && KW == 1 && pad == 0 ? 2 : 0, al, tile, L, s);
   }
 
   ConvGeom geo;
