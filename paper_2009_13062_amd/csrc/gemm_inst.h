@@ -29,10 +29,12 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_mfma_kernel(GemmArgs a) {
   const long cvo = z0 * a.ep.col_vec_stride0 + z1 * a.ep.col_vec_stride1 + col0;
   const bf16_t* Abase = a.A + z0 * a.sA0 + z1 * a.sA1 + (long)row0 * a.lda;
   const bf16_t* Bbase = a.B + z0 * a.sB0 + z1 * a.sB1;
-  if constexpr (BKIND == 0 || BKIND == 2) {
+  if constexpr (BKIND == 0 || BKIND == 2 || BKIND == 22 || BKIND == 24) {
     ATileLoader<Cfg::kBM, ALIGN_A, false, Cfg::kThreads> la;
     la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
-    typename std::conditional<BKIND == 0, BIm2colLoader<Cfg::kBN, Cfg::kThreads>, BStridedPointwiseLoader<Cfg::kBN, Cfg::kThreads>>::type lb;
+    using Pairs = BStride2PairLoader<Cfg::kBN, BKIND == 24 ? 4 : 2, Cfg::kThreads>;
+    using Strided = typename std::conditional<BKIND == 2, BStridedPointwiseLoader<Cfg::kBN, Cfg::kThreads>, Pairs>::type;
+    typename std::conditional<BKIND == 0, BIm2colLoader<Cfg::kBN, Cfg::kThreads>, Strided>::type lb;
     lb.xg = Bbase; lb.g = a.geom; lb.cols_left = cols_left; lb.K = a.K; lb.col0 = col0;
     gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
   } else {

@@ -289,6 +289,64 @@ struct BStridedPointwiseLoader {
   }
 };
 
+// The same for stride 2 over an image of even width W = 2 Wo, read as (even, odd) pixel pairs: pair
+// oy * W + ox of a plane holds input pixel (2 oy, 2 ox) in its low half, so VW consecutive output
+// positions of one row are VW consecutive pairs, fetched with one 4*VW-byte load (VW = 4 or 2, dividing
+// Wo, hence no group straddles a row) and narrowed by byte permutes.  The caller guarantees the alignment:
+// plane pitch and base multiples of 2*VW elements.
+template <int BN, int VW, int NT>
+struct BStride2PairLoader {
+  static_assert(VW == 4 || VW == 2, "pairs per load");
+  static constexpr int kPitch = BN + kPadB;
+  static constexpr int kPerRow = BN / 8;
+  static constexpr int kTasks = kBK * kPerRow;
+  static constexpr int kPer = kTasks / NT;
+  static_assert(kTasks % NT == 0, "tile too small for the workgroup");
+  const bf16_t* xg;     // first input plane of this group and image
+  Im2colGeom g;
+  int cols_left, K, col0;
+  struct Regs { uint4 v[kPer]; };
+
+  __device__ __forceinline__ void fetch(Regs& regs, int k0, int tid) const {
+    constexpr uint32_t kLowHalves = 0x05040100u;     // perm(hi, lo): low 16 bits of lo, then low 16 bits of hi
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int task = tid + t * NT;
+      const int k = k0 + task / kPerRow, j = (task % kPerRow) * 8;
+      uint32_t o[4] = {0u, 0u, 0u, 0u};
+      if (k < K && j < cols_left) {
+        const uint32_t* plane = reinterpret_cast<const uint32_t*>(xg + (long)k * g.H * g.W);
+        const int p = col0 + j;
+        int oy = p / g.Wo, ox = p - oy * g.Wo;
+#pragma unroll
+        for (int q = 0; q < 8 / VW; ++q) {
+          if (j + q * VW < cols_left) {            // the output count is a multiple of VW: whole groups only
+            const uint32_t* src = plane + oy * g.W + ox;
+            if constexpr (VW == 4) {
+              const uint4 v = *reinterpret_cast<const uint4*>(src);
+              o[2 * q] = __builtin_amdgcn_perm(v.y, v.x, kLowHalves);
+              o[2 * q + 1] = __builtin_amdgcn_perm(v.w, v.z, kLowHalves);
+            } else {
+              const uint2 v = *reinterpret_cast<const uint2*>(src);
+              o[q] = __builtin_amdgcn_perm(v.y, v.x, kLowHalves);
+            }
+          }
+          ox += VW;
+          if (ox == g.Wo) { ox = 0; ++oy; }
+        }
+      }
+      regs.v[t] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+  __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int task = tid + t * NT;
+      lds_store16(lds + (task / kPerRow) * kPitch + (task % kPerRow) * 8, regs.v[t]);
+    }
+  }
+};
+
 // ------------------------------------------------------------------------------------------
 // The tile main loop and epilogue
 // ------------------------------------------------------------------------------------------

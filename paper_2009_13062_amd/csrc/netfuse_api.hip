@@ -51,6 +51,8 @@ inline unsigned grid_for(long long total, int per_block, long long cap = 1 << 20
 nf_status launch_gemm_any(int bkind, int align_a, int tile, GemmLaunch& L, hipStream_t s) {
   switch (bkind) {
     case 8: return launch_gemm_bkind<8>(align_a, tile, L, s);
+    case 24: return launch_gemm_bkind<24>(align_a, tile, L, s);
+    case 22: return launch_gemm_bkind<22>(align_a, tile, L, s);
     case 2: return launch_gemm_bkind<2>(align_a, tile, L, s);
     case 1: return launch_gemm_bkind<1>(align_a, tile, L, s);
     case 0: return launch_gemm_bkind<0>(align_a, tile, L, s);
@@ -314,7 +316,17 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     }
     a.geom.H = H; a.geom.W = W; a.geom.KH = KH; a.geom.KW = KW; a.geom.Wo = (int)Wo;
     a.geom.stride = stride; a.geom.pad = pad; a.geom.dil = dilation;
-    return launch_gemm_any(KH == 1 && KW == 1 && pad == 0 ? 2 : 0, al, tile, L, s);
+    int bkind = 0;
+    if (KH == 1 && KW == 1 && pad == 0) {
+      // projection shortcuts; stride 2 over an even width is read as aligned pixel pairs where the shape allows
+      bkind = 2;
+      const long long plane = (long long)H * W;
+      if (stride == 2 && W == 2 * Wo) {
+        if (Wo % 4 == 0 && plane % 8 == 0 && aligned(x, 16)) bkind = 24;
+        else if (Wo % 2 == 0 && plane % 4 == 0 && aligned(x, 8)) bkind = 22;
+      }
+    }
+    return launch_gemm_any(bkind, al, tile, L, s);
   }
 
   ConvGeom geo;

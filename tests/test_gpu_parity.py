@@ -138,7 +138,12 @@ CONV_CASES = [
     (3, 1, 64, 256, 1, 14, 14, 1, 1, 1, 0, 1),     # pointwise, HW = 196 (8-byte rows)
     (2, 1, 128, 96, 1, 7, 7, 1, 1, 1, 0, 1),       # pointwise, HW = 49 (2-byte rows)
     (2, 1, 3, 64, 1, 32, 32, 7, 7, 2, 3, 1),       # stem: Cin 3, K = 147 (odd rows of weights)
-    (2, 1, 128, 256, 1, 16, 16, 1, 1, 2, 0, 1),    # strided projection shortcut
+    (2, 1, 128, 256, 1, 16, 16, 1, 1, 2, 0, 1),    # strided projection shortcut, Wo % 4 == 0: 4 pixel pairs per load
+    (2, 2, 72, 96, 1, 24, 40, 1, 1, 2, 0, 1),      # the same, non-square, K not a multiple of the k step, ragged columns
+    (3, 1, 64, 128, 1, 14, 28, 1, 1, 2, 0, 1),     # strided projection, Wo = 14: 2 pixel pairs per load
+    (2, 1, 64, 128, 1, 14, 14, 1, 1, 2, 0, 1),     # strided projection, Wo = 7: element gather
+    (2, 1, 64, 128, 1, 15, 15, 1, 1, 2, 0, 1),     # strided projection, odd width
+    (2, 1, 64, 64, 1, 12, 12, 1, 1, 3, 0, 1),      # pointwise, stride 3
     (2, 1, 64, 64, 1, 16, 16, 3, 3, 2, 1, 1),      # strided 3x3
     (2, 1, 128, 128, 32, 14, 14, 3, 3, 1, 1, 1),   # ResNeXt: 4 channels per group, 64 groups merged
     (2, 2, 32, 64, 4, 9, 11, 3, 3, 1, 1, 1),       # batch 2 per model, non-square image
