@@ -38,6 +38,19 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_mfma_kernel(GemmArgs a) {
     lb.xg = Bbase; lb.g = a.geom; lb.cols_left = cols_left; lb.K = a.K; lb.col0 = col0;
     gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
   } else {
+    if constexpr (Cfg::kDepth > 1 && ALIGN_A == 16) {
+      // long k extents stream through the deep pipeline when its branch-free loads stay inside the operands
+      const bf16_t* Bt = Bbase + col0;
+      const int lastc = BDeepLoader<Cfg::kBN, BKIND == 8, Cfg::kThreads>::last_chunk(cols_left);
+      if (a.K % (kBK * Cfg::kDepth) == 0 && Bt + (long)(a.K - 1) * a.ldb + lastc + 8 <= a.B_end) {
+        ADeepLoader<Cfg::kBM, Cfg::kThreads> la;
+        la.init(Abase, a.lda, rows_left, threadIdx.x);
+        BDeepLoader<Cfg::kBN, BKIND == 8, Cfg::kThreads> lb;
+        lb.init(Bt, a.ldb, cols_left, threadIdx.x);
+        gemm_tile<Cfg, true>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
+        return;
+      }
+    }
     auto general = [&]() {
       ATileLoader<Cfg::kBM, ALIGN_A, false, Cfg::kThreads> la;
       la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
@@ -86,12 +99,15 @@ nf_status launch_gemm(GemmLaunch& L, hipStream_t s) {
 
 template <int ALIGN_A, int BKIND>
 nf_status launch_gemm_tile(int tile, GemmLaunch& L, hipStream_t s) {
+  // depth of the load pipeline for the dense B kinds (the gathering loaders keep one step in flight)
+  constexpr bool kDense = BKIND == 8 || BKIND == 1;
+  constexpr int D2 = kDense ? 2 : 1, D4 = kDense ? 4 : 1;
   switch (tile) {
-    case T128x128: return launch_gemm<TileCfg<128, 128, 2, 2>, ALIGN_A, BKIND>(L, s);
-    case T64x128: return launch_gemm<TileCfg<64, 128, 2, 2>, ALIGN_A, BKIND>(L, s);
-    case T64x64: return launch_gemm<TileCfg<64, 64, 2, 2>, ALIGN_A, BKIND>(L, s);
-    case T32x128: return launch_gemm<TileCfg<32, 128, 1, 4>, ALIGN_A, BKIND>(L, s);
-    case T128x128w8: return launch_gemm<TileCfg<128, 128, 2, 4>, ALIGN_A, BKIND>(L, s);
+    case T128x128: return launch_gemm<TileCfg<128, 128, 2, 2, D2>, ALIGN_A, BKIND>(L, s);
+    case T64x128: return launch_gemm<TileCfg<64, 128, 2, 2, D2>, ALIGN_A, BKIND>(L, s);
+    case T64x64: return launch_gemm<TileCfg<64, 64, 2, 2, D4>, ALIGN_A, BKIND>(L, s);
+    case T32x128: return launch_gemm<TileCfg<32, 128, 1, 4, D2>, ALIGN_A, BKIND>(L, s);
+    case T128x128w8: return launch_gemm<TileCfg<128, 128, 2, 4, D2>, ALIGN_A, BKIND>(L, s);
   }
   return NF_EUNSUPPORTED;
 }

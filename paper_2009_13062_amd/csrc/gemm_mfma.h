@@ -348,10 +348,86 @@ struct BStride2PairLoader {
 };
 
 // ------------------------------------------------------------------------------------------
+// Branch-free loaders of the deep pipeline (gemm_tile_deep): every fetch issues the same loads on every
+// lane, so the number of loads in flight is known at compile time and a wait for one k-step leaves the
+// younger steps pending.  Rows and column chunks outside the problem are redirected to the last valid
+// one instead of being skipped; what they produce lands in rows / columns of C that are never stored.
+// Requirements (checked by the caller): K a multiple of the k-step, A rows 16-byte aligned, and for B
+// the last chunk of the last k row inside the operand.
+// ------------------------------------------------------------------------------------------
+template <int BM, int NT>
+struct ADeepLoader {
+  static constexpr int kChunks = BM * (kBK / 8);
+  static constexpr int kPer = kChunks / NT;
+  static_assert(kChunks % NT == 0, "tile too small for the workgroup");
+  const bf16_t* src[kPer];              // this thread's chunks at k = 0
+  struct Regs { uint4 v[kPer]; };
+  __device__ __forceinline__ void init(const bf16_t* base, long lda, int rows_left, int tid) {
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int c = tid + t * NT;
+      const int r = min(c / 8, rows_left - 1);
+      src[t] = base + (long)r * lda + (c % 8) * 8;
+    }
+  }
+  __device__ __forceinline__ void fetch(Regs& regs, int k0, int) const {
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) regs.v[t] = *reinterpret_cast<const uint4*>(src[t] + k0);
+  }
+  __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int c = tid + t * NT;
+      lds_store16(lds + (c / 8) * kPitchA + (c % 8) * 8, regs.v[t]);
+    }
+  }
+};
+
+template <int BN, bool ALIGNED, int NT>
+struct BDeepLoader {
+  static constexpr int kPitch = BN + kPadB;
+  static constexpr int kPerRow = BN / 8;
+  static constexpr int kTasks = kBK * kPerRow;
+  static constexpr int kPer = kTasks / NT;
+  static_assert(kTasks % NT == 0, "tile too small for the workgroup");
+  const bf16_t* src[kPer];              // this thread's chunks at k = 0
+  long step;                            // elements per k-step: kBK * ldb
+  struct Regs { uint4 v[kPer]; };
+  struct __attribute__((packed, aligned(2))) unaligned16 { uint4 v; };
+  // first column of the last chunk that holds a valid column
+  static __device__ __forceinline__ int last_chunk(int cols_left) { return (min(cols_left, BN) - 1) & ~7; }
+  __device__ __forceinline__ void init(const bf16_t* base, long ldb, int cols_left, int tid) {
+    step = (long)kBK * ldb;
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int task = tid + t * NT;
+      const int j = min((task % kPerRow) * 8, last_chunk(cols_left));
+      src[t] = base + (long)(task / kPerRow) * ldb + j;
+    }
+  }
+  __device__ __forceinline__ void fetch(Regs& regs, int k0, int) const {
+    const long off = (long)(k0 / kBK) * step;
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      if constexpr (ALIGNED) regs.v[t] = *reinterpret_cast<const uint4*>(src[t] + off);
+      else regs.v[t] = reinterpret_cast<const unaligned16*>(src[t] + off)->v;
+    }
+  }
+  __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int task = tid + t * NT;
+      lds_store16(lds + (task / kPerRow) * kPitch + (task % kPerRow) * 8, regs.v[t]);
+    }
+  }
+};
+
+// ------------------------------------------------------------------------------------------
 // The tile main loop and epilogue
 // ------------------------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int DEPTH = 1>
 struct TileCfg {
+  static constexpr int kDepth = DEPTH;     // k-steps of global loads in flight per thread (see gemm_tile_deep)
   static_assert(WGM * WGN == 4 || WGM * WGN == 8, "4 or 8 wavefronts per workgroup");
   static constexpr int kBM = BM, kBN = BN, kWGM = WGM, kWGN = WGN;
   static constexpr int kThreads = WGM * WGN * kWave;
@@ -503,7 +579,9 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[Cfg::FM][Cfg::FN],
 #undef NF_EPI
 }
 
-template <class Cfg, class ALoader, class BLoader>
+// DEEP: the loaders are branch free and K is a multiple of Cfg::kDepth k-steps; Cfg::kDepth steps of
+// loads are kept in flight in a ring of register slots.
+template <class Cfg, bool DEEP = false, class ALoader, class BLoader>
 __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_bf16_t* smem,
                                           bf16_t* C, const bf16_t* R, long ldc, int rows_left,
                                           int cols_left, const Epilogue& ep, long row_vec_off,
@@ -559,6 +637,48 @@ __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_b
   // Software pipeline: while k-step kt is multiplied out of LDS stage kt % 2, the global loads of
   // step kt+1 are in flight into registers; they are committed to the other stage afterwards.
   const int nk = (K + kBK - 1) / kBK;
+  if constexpr (DEEP) {
+    // While step kt is multiplied out of LDS, the loads of steps kt+1 .. kt+D sit in D register slots.
+    // The steady loop is unrolled D times (static slot indices; D even, so the LDS stage is static too)
+    // and issues unconditionally, so the wait before each commit is for exactly one step; the last D
+    // steps drain the ring without issuing.
+    constexpr int D = Cfg::kDepth;
+    static_assert(D >= 2 && D % 2 == 0, "even depth");
+    typename ALoader::Regs ra[D];
+    typename BLoader::Regs rb[D];
+#pragma unroll
+    for (int u = 0; u < D; ++u) {
+      la.fetch(ra[u], u * kBK, tid);
+      lb.fetch(rb[u], u * kBK, tid);
+    }
+    la.commit(ra[0], As, tid);
+    lb.commit(rb[0], Bs, tid);
+    __syncthreads();
+    int kt0 = 0;
+    for (; kt0 + D < nk; kt0 += D) {
+#pragma unroll
+      for (int u = 0; u < D; ++u) {
+        la.fetch(ra[u], (kt0 + u + D) * kBK, tid);        // slot u is free: its step went to LDS one step ago
+        lb.fetch(rb[u], (kt0 + u + D) * kBK, tid);
+        __builtin_amdgcn_sched_barrier(0);                 // the loads go out before anything waits
+        multiply_stage(u & 1);
+        la.commit(ra[(u + 1) % D], As + ((u + 1) & 1) * Cfg::kLdsA, tid);
+        lb.commit(rb[(u + 1) % D], Bs + ((u + 1) & 1) * Cfg::kLdsB, tid);
+        __syncthreads();
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < D; ++u) {
+      multiply_stage(u & 1);
+      if (u + 1 < D) {
+        la.commit(ra[u + 1], As + ((u + 1) & 1) * Cfg::kLdsA, tid);
+        lb.commit(rb[u + 1], Bs + ((u + 1) & 1) * Cfg::kLdsB, tid);
+      }
+      __syncthreads();
+    }
+    gemm_epilogue<Cfg>(acc, (lds_f32_t*)smem, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off);
+    return;
+  }
   typename ALoader::Regs ra;
   typename BLoader::Regs rb;
   la.fetch(ra, 0, tid);
