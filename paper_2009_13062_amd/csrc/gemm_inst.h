@@ -39,14 +39,12 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_mfma_kernel(GemmArgs a) {
     gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
   } else {
     if constexpr (Cfg::kDepth > 1 && ALIGN_A == 16) {
-      // long k extents stream through the deep pipeline when its branch-free loads stay inside the operands
-      const bf16_t* Bt = Bbase + col0;
-      const int lastc = BDeepLoader<Cfg::kBN, BKIND == 8, Cfg::kThreads>::last_chunk(cols_left);
-      if (a.K % (kBK * Cfg::kDepth) == 0 && Bt + (long)(a.K - 1) * a.ldb + lastc + 8 <= a.B_end) {
+      // whole k-step multiples stream through the deep pipeline
+      if (a.K % (kBK * Cfg::kDepth) == 0 && a.ldb >= 8) {
         ADeepLoader<Cfg::kBM, Cfg::kThreads> la;
         la.init(Abase, a.lda, rows_left, threadIdx.x);
         BDeepLoader<Cfg::kBN, BKIND == 8, Cfg::kThreads> lb;
-        lb.init(Bt, a.ldb, cols_left, threadIdx.x);
+        lb.init(Bbase + col0, a.ldb, cols_left, a.K, a.B_end, threadIdx.x);
         gemm_tile<Cfg, true>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
         return;
       }

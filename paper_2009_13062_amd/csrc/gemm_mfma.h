@@ -352,8 +352,8 @@ struct BStride2PairLoader {
 // lane, so the number of loads in flight is known at compile time and a wait for one k-step leaves the
 // younger steps pending.  Rows and column chunks outside the problem are redirected to the last valid
 // one instead of being skipped; what they produce lands in rows / columns of C that are never stored.
-// Requirements (checked by the caller): K a multiple of the k-step, A rows 16-byte aligned, and for B
-// the last chunk of the last k row inside the operand.
+// Requirements (checked by the caller): K a multiple of the k-step, A rows 16-byte aligned, B rows of
+// at least 8 elements.
 // ------------------------------------------------------------------------------------------
 template <int BM, int NT>
 struct ADeepLoader {
@@ -392,25 +392,45 @@ struct BDeepLoader {
   static_assert(kTasks % NT == 0, "tile too small for the workgroup");
   const bf16_t* src[kPer];              // this thread's chunks at k = 0
   long step;                            // elements per k-step: kBK * ldb
+  // !ALIGNED: rows start at any 2-byte address and the last chunk of a row may run into the next row.
+  // Only in the last row of the whole operand would it run past the end: that one load is pulled back to
+  // `limit` (last address a full chunk may start at) and the elements it should have brought are put into
+  // LDS one by one by finish(), after the last k-step is committed.
+  const bf16_t* limit;
+  const bf16_t* tail_src;               // valid elements of that chunk, or null when the tile does not reach the end
+  int tail_n, tail_col;
   struct Regs { uint4 v[kPer]; };
   struct __attribute__((packed, aligned(2))) unaligned16 { uint4 v; };
   // first column of the last chunk that holds a valid column
   static __device__ __forceinline__ int last_chunk(int cols_left) { return (min(cols_left, BN) - 1) & ~7; }
-  __device__ __forceinline__ void init(const bf16_t* base, long ldb, int cols_left, int tid) {
+  // ldb >= 8, K a multiple of kBK; `end` = one past the last element of the whole operand
+  __device__ __forceinline__ void init(const bf16_t* base, long ldb, int cols_left, int K, const bf16_t* end, int tid) {
     step = (long)kBK * ldb;
+    const int lastc = last_chunk(cols_left);
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
       const int task = tid + t * NT;
-      const int j = min((task % kPerRow) * 8, last_chunk(cols_left));
+      const int j = min((task % kPerRow) * 8, lastc);
       src[t] = base + (long)(task / kPerRow) * ldb + j;
+    }
+    if constexpr (!ALIGNED) {
+      limit = end - 8;
+      const bf16_t* last = base + (long)(K - 1) * ldb + lastc;    // with ldb >= 8 no other chunk can cross the end
+      tail_src = last > limit ? last : nullptr;
+      tail_n = (int)(end - last);
+      tail_col = lastc;
     }
   }
   __device__ __forceinline__ void fetch(Regs& regs, int k0, int) const {
     const long off = (long)(k0 / kBK) * step;
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
-      if constexpr (ALIGNED) regs.v[t] = *reinterpret_cast<const uint4*>(src[t] + off);
-      else regs.v[t] = reinterpret_cast<const unaligned16*>(src[t] + off)->v;
+      if constexpr (ALIGNED) {
+        regs.v[t] = *reinterpret_cast<const uint4*>(src[t] + off);
+      } else {
+        const bf16_t* p = src[t] + off;
+        regs.v[t] = reinterpret_cast<const unaligned16*>(p < limit ? p : limit)->v;
+      }
     }
   }
   __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int tid) const {
@@ -418,6 +438,17 @@ struct BDeepLoader {
     for (int t = 0; t < kPer; ++t) {
       const int task = tid + t * NT;
       lds_store16(lds + (task / kPerRow) * kPitch + (task % kPerRow) * 8, regs.v[t]);
+    }
+  }
+  // after the commit of the last k-step into `lds`, before the barrier that publishes it
+  __device__ __forceinline__ void finish(lds_bf16_t* lds, int tid) const {
+    if constexpr (!ALIGNED) {
+      if (tail_src == nullptr) return;
+      // the thread that committed the pulled-back chunk overwrites it (LDS writes of one thread stay in order)
+#pragma unroll
+      for (int t = 0; t < kPer; ++t)
+        if (tid + t * NT == (kBK - 1) * kPerRow + tail_col / 8)
+          for (int e = 0; e < tail_n; ++e) lds[(kBK - 1) * kPitch + tail_col + e] = tail_src[e];
     }
   }
 };
@@ -673,6 +704,7 @@ __device__ __forceinline__ void gemm_tile(ALoader& la, BLoader& lb, int K, lds_b
       if (u + 1 < D) {
         la.commit(ra[u + 1], As + ((u + 1) & 1) * Cfg::kLdsA, tid);
         lb.commit(rb[u + 1], Bs + ((u + 1) & 1) * Cfg::kLdsB, tid);
+        if (u + 2 == D) lb.finish(Bs + ((u + 1) & 1) * Cfg::kLdsB, tid);      // that was the last k-step
       }
       __syncthreads();
     }

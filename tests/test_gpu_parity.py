@@ -91,6 +91,9 @@ LIN_CASES = [
     (4, 7, 9, 11, False, True, 0),           # odd everything: element-wise loaders
     (2, 300, 72, 136, False, False, 0),      # K not a multiple of 64
     (32, 8, 64, 64, True, False, 0),
+    (3, 70, 256, 100, True, True, 0),        # deep load pipeline, weight rows at odd 4-byte addresses, last chunk crosses the operand end
+    (2, 200, 512, 77, True, False, 2),       # the same with rows at 2-byte addresses and the 8-wave tile
+    (2, 96, 256, 256, True, True, 0),        # deep pipeline, aligned
 ]
 
 
@@ -137,6 +140,10 @@ CONV_CASES = [
     (2, 1, 64, 128, 1, 28, 28, 1, 1, 1, 0, 1),     # pointwise, HW % 8 == 0
     (3, 1, 64, 256, 1, 14, 14, 1, 1, 1, 0, 1),     # pointwise, HW = 196 (8-byte rows)
     (2, 1, 128, 96, 1, 7, 7, 1, 1, 1, 0, 1),       # pointwise, HW = 49 (2-byte rows)
+    (3, 2, 256, 96, 1, 7, 7, 1, 1, 1, 0, 1),       # the same through the deep load pipeline (K % 256 == 0): last chunk of the last plane
+    (2, 1, 512, 192, 1, 14, 14, 1, 1, 1, 0, 1),    # deep pipeline, HW = 196, two column tiles
+    (2, 1, 256, 64, 1, 3, 3, 1, 1, 1, 0, 1),       # deep pipeline, rows of 9 elements
+    (2, 1, 256, 64, 1, 2, 3, 1, 1, 1, 0, 1),       # rows shorter than a chunk: the deep pipeline does not apply
     (2, 1, 3, 64, 1, 32, 32, 7, 7, 2, 3, 1),       # stem: Cin 3, K = 147 (odd rows of weights)
     (2, 1, 128, 256, 1, 16, 16, 1, 1, 2, 0, 1),    # strided projection shortcut, Wo % 4 == 0: 4 pixel pairs per load
     (2, 2, 72, 96, 1, 24, 40, 1, 1, 2, 0, 1),      # the same, non-square, K not a multiple of the k step, ragged columns
