@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnetfuse.so")
-SOURCES = ["netfuse_api.hip", "gemm_inst_b8.hip", "gemm_inst_b2.hip", "gemm_inst_b24.hip", "gemm_inst_b22.hip", "gemm_inst_b1.hip",
+SOURCES = ["netfuse_api.hip", "gemm_inst_b8.hip", "gemm_inst_b2.hip", "gemm_inst_b24.hip", "gemm_inst_b22.hip", "gemm_inst_b21.hip", "gemm_inst_b1.hip",
            "gemm_inst_b0.hip", "gemm_inst_dma.hip", "conv_patch_inst.hip"]
 
 HIPCC_FLAGS = [
@@ -53,7 +53,7 @@ def _compile(src: str, extra, verbose: bool, force: bool) -> str:
     return obj
 
 
-def build(verbose: bool = False, extra=(), force: bool = True, jobs: int = 7) -> str:
+def build(verbose: bool = False, extra=(), force: bool = True, jobs: int = 8) -> str:
     """Compile every translation unit (always, unless force=False and objects are newer) and link."""
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:

@@ -453,6 +453,74 @@ struct BDeepLoader {
   }
 };
 
+// Branch-free B loader of a stride-2 pointwise convolution over an image of even width W = 2 Wo, for the
+// deep pipeline: the image is read as (even, odd) pixel pairs (see BStride2PairLoader), VW pairs per load
+// (VW = 4, 2 or 1; VW divides Wo, and plane pitch and base are multiples of 2*VW elements).  The pair
+// offsets of this thread's 8 / VW loads per task are fixed at init; output positions past the end of the
+// image are redirected to the last group of VW.
+template <int BN, int VW, int NT>
+struct BPairDeepLoader {
+  static_assert(VW == 4 || VW == 2 || VW == 1, "pairs per load");
+  static constexpr int kPitch = BN + kPadB;
+  static constexpr int kPerRow = BN / 8;
+  static constexpr int kTasks = kBK * kPerRow;
+  static constexpr int kPer = kTasks / NT;
+  static constexpr int kLoads = 8 / VW;             // per task
+  static_assert(kTasks % NT == 0, "tile too small for the workgroup");
+  typedef typename std::conditional<VW == 4, uint4, typename std::conditional<VW == 2, uint2, uint32_t>::type>::type raw_t;
+  const uint32_t* planes;                // first input plane of this group and image, as pairs
+  int off[kPer][kLoads];                 // pair offsets at k = 0
+  int step;                              // pairs per k-step: kBK * H * W / 2
+  struct Regs { raw_t v[kPer][kLoads]; };
+  __device__ __forceinline__ void init(const bf16_t* xg, const Im2colGeom& g, int col0, int cols_left, int tid) {
+    planes = reinterpret_cast<const uint32_t*>(xg);
+    const int plane = g.H * g.W / 2;
+    step = kBK * plane;
+    const int p_last = col0 + cols_left - VW;        // first position of the last whole group
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int task = tid + t * NT;
+      const int krow = task / kPerRow, j = (task % kPerRow) * 8;
+#pragma unroll
+      for (int q = 0; q < kLoads; ++q) {
+        const int p = min(col0 + j + q * VW, p_last);
+        const int oy = p / g.Wo, ox = p - oy * g.Wo;
+        off[t][q] = krow * plane + oy * g.W + ox;
+      }
+    }
+  }
+  __device__ __forceinline__ void fetch(Regs& regs, int k0, int) const {
+    const uint32_t* base = planes + (long)(k0 / kBK) * step;
+#pragma unroll
+    for (int t = 0; t < kPer; ++t)
+#pragma unroll
+      for (int q = 0; q < kLoads; ++q) regs.v[t][q] = *reinterpret_cast<const raw_t*>(base + off[t][q]);
+  }
+  __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int tid) const {
+    constexpr uint32_t kLowHalves = 0x05040100u;     // perm(hi, lo): low 16 bits of lo, then low 16 bits of hi
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int task = tid + t * NT;
+      uint32_t o[4];
+      if constexpr (VW == 4) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          o[2 * q] = __builtin_amdgcn_perm(regs.v[t][q].y, regs.v[t][q].x, kLowHalves);
+          o[2 * q + 1] = __builtin_amdgcn_perm(regs.v[t][q].w, regs.v[t][q].z, kLowHalves);
+        }
+      } else if constexpr (VW == 2) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) o[q] = __builtin_amdgcn_perm(regs.v[t][q].y, regs.v[t][q].x, kLowHalves);
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) o[q] = __builtin_amdgcn_perm(regs.v[t][2 * q + 1], regs.v[t][2 * q], kLowHalves);
+      }
+      lds_store16(lds + (task / kPerRow) * kPitch + (task % kPerRow) * 8, make_uint4(o[0], o[1], o[2], o[3]));
+    }
+  }
+  __device__ __forceinline__ void finish(lds_bf16_t*, int) const {}
+};
+
 // ------------------------------------------------------------------------------------------
 // The tile main loop and epilogue
 // ------------------------------------------------------------------------------------------
