@@ -44,6 +44,8 @@ nf_status launch_gemm_bkind(int align_a, int tile, GemmLaunch& L, hipStream_t s)
 struct ConvPatchArgs;
 // 3x3 convolution through the LDS patch-gather kernel (conv_patch.h); see netfuse_conv2d for the conditions.
 nf_status launch_conv_patch_3x3(ConvPatchArgs& a, int B, hipStream_t s);
+// the same layers through the tap-major kernel (conv_tap.h) where it applies; NF_EUNSUPPORTED = it does not
+nf_status launch_conv_tap_3x3(ConvPatchArgs& a, int B, hipStream_t s);
 struct ConvStemArgs;
 // 7x7 / stride 2 / pad 3 over 3 input channels per group (conv_stem.h)
 nf_status launch_conv_stem(ConvStemArgs& a, int B, hipStream_t s);

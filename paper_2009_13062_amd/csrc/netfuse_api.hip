@@ -312,6 +312,11 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
       c.y_group = (long)cog_e * HoWo; c.y_image = (long)Ctot_out * HoWo;
       c.ep = a.ep;
       c.ep.row_vec_stride0 = cog_e;
+      static const bool no_tap = getenv("NETFUSE_NO_TAP") != nullptr;
+      if (!no_tap) {
+        const nf_status st = launch_conv_tap_3x3(c, B, s);
+        if (st != NF_EUNSUPPORTED) return st;
+      }
       return launch_conv_patch_3x3(c, B, s);
     }
     a.geom.H = H; a.geom.W = W; a.geom.KH = KH; a.geom.KW = KW; a.geom.Wo = (int)Wo;

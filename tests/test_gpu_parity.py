@@ -161,6 +161,10 @@ CONV_CASES = [
     (1, 1, 64, 64, 1, 56, 56, 3, 3, 1, 1, 1),      # patch-gather, 58-wide patch, tiles that start mid-row
     (2, 1, 64, 128, 1, 30, 30, 3, 3, 2, 1, 1),     # patch-gather, stride 2, odd output width 15
     (2, 1, 48, 64, 1, 12, 12, 3, 3, 1, 0, 1),      # patch-gather, no padding, 3 channel blocks
+    (2, 2, 64, 80, 1, 7, 7, 3, 3, 1, 1, 1),        # tap-major 3x3: 1-pixel chunks, ragged row tile, batch 2
+    (2, 1, 96, 64, 1, 12, 20, 3, 3, 1, 0, 1),      # tap-major 3x3: 3 channel blocks, no padding, non-square, 4-pixel chunks
+    (1, 1, 32, 32, 1, 28, 28, 3, 3, 2, 1, 1),      # tap-major 3x3: stride 2, three patch tasks per thread
+    (1, 1, 32, 64, 1, 56, 56, 3, 3, 2, 1, 1),      # tap-major 3x3: stride 2, 8-pixel chunks, two patch tasks per thread
     (3, 1, 64, 64, 8, 28, 28, 3, 3, 1, 1, 1),      # fused narrow groups: 8 channels per group, 4 groups per block
     (2, 2, 64, 64, 4, 16, 16, 3, 3, 2, 1, 1),      # fused narrow groups: 16 per group, stride 2, batch 2
     (1, 1, 32, 32, 8, 56, 56, 3, 3, 1, 1, 1),      # fused narrow groups: 4 per group on a 56x56 image
