@@ -52,7 +52,10 @@ struct ConvTapCfg {
 };
 
 // VW: pixels per patch chunk (= a.VW; VW | W).  NT: patch tasks per thread (the host checks the bound).
-template <class Cfg, int VW, int NT>
+// FUSED: S > 1 narrow groups (4, 8 or 16 channels each) share the single 32-channel block: the weight tile
+// is block diagonal (row r carries its own group's channels at channel offset (r / cog_real) * cig_real,
+// zeros elsewhere), filled once; see conv_patch.h for why no product crosses a group.
+template <class Cfg, int VW, int NT, bool FUSED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWaves))) void conv_tap_kernel(ConvPatchArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   lds_bf16_t* As = (lds_bf16_t*)smem_raw;
@@ -132,7 +135,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
   auto prefetch = [&](int ci0) {
 #pragma unroll
     for (int t = 0; t < Cfg::kWPer; ++t) {
-      if (w_dst[t] < 0) continue;
+      if (FUSED || w_dst[t] < 0) continue;
       const bf16_t* p = wg + w_off[t] + (long)ci0 * 9;
 #pragma unroll
       for (int q = 0; q < 9; ++q) {
@@ -168,7 +171,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
   auto commit = [&]() {
 #pragma unroll
     for (int t = 0; t < Cfg::kWPer; ++t) {
-      if (w_dst[t] < 0) continue;
+      if (FUSED || w_dst[t] < 0) continue;
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap) {
         uint32_t o[4];
@@ -195,7 +198,54 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
   };
 
   prefetch(0);
-  __syncthreads();                                         // the zero fill is complete
+  if constexpr (FUSED) {
+    for (int c = tid; c < Cfg::kBM * Cfg::kAPitch / 8; c += 256) lds_store16(As + c * 8, make_uint4(0, 0, 0, 0));
+    __syncthreads();
+    // task = (row, run of cw = 8 or 4 channels of the row's group): 9*cw contiguous weights, written as one
+    // vector of cw channels per tap
+    const int cw = a.cig_real >= 8 ? 8 : 4, subs = a.cig_real / cw;
+    const bf16_t* ws = a.w + (long)G * a.cog * a.cig_real * 9;       // fused group G: rows G*cog .. of the weight tensor
+    for (int task = tid; task < a.cog * subs; task += 256) {
+      const int r = task / subs, sub = task - r * subs;
+      const bf16_t* p = ws + ((long)r * a.cig_real + sub * cw) * 9;
+      lds_bf16_t* dst = As + r * Cfg::kAPitch + (r / a.cog_real) * a.cig_real + sub * cw;
+      uint32_t d[36];
+      if (cw == 8) {
+#pragma unroll
+        for (int q = 0; q < 9; ++q) {
+          const uint4 v = *reinterpret_cast<const uint4*>(p + q * 8);
+          d[4 * q] = v.x; d[4 * q + 1] = v.y; d[4 * q + 2] = v.z; d[4 * q + 3] = v.w;
+        }
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+          uint32_t o[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int e0 = 9 * (2 * q) + tap, e1 = 9 * (2 * q + 1) + tap;
+            o[q] = __builtin_amdgcn_perm(d[e1 / 2], d[e0 / 2], pick(e0 % 2, e1 % 2));
+          }
+          lds_store16(dst + tap * CB, make_uint4(o[0], o[1], o[2], o[3]));
+        }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 9; ++q) {
+          const uint2 v = *reinterpret_cast<const uint2*>(p + q * 4);
+          d[2 * q] = v.x; d[2 * q + 1] = v.y;
+        }
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+          uint32_t o[2];
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            const int e0 = 9 * (2 * q) + tap, e1 = 9 * (2 * q + 1) + tap;
+            o[q] = __builtin_amdgcn_perm(d[e1 / 2], d[e0 / 2], pick(e0 % 2, e1 % 2));
+          }
+          lds_store8(dst + tap * CB, o[0], o[1]);
+        }
+      }
+    }
+  }
+  __syncthreads();                                         // the zero fills are complete
   for (int ci0 = 0; ci0 < a.cig; ci0 += CB) {
     commit();
     __syncthreads();

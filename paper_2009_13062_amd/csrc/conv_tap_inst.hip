@@ -7,9 +7,9 @@
 
 namespace nf {
 
-template <class Cfg, int VW, int NT>
+template <class Cfg, int VW, int NT, bool FUSED>
 static nf_status launch_tap_kernel(long long total, int lds, const ConvPatchArgs& a, hipStream_t s) {
-  auto kern = conv_tap_kernel<Cfg, VW, NT>;
+  auto kern = conv_tap_kernel<Cfg, VW, NT, FUSED>;
   if (lds > 64 * 1024) {
     static std::atomic<bool> opted_in{false};        // per kernel: idempotent, a benign race
     if (!opted_in.load(std::memory_order_acquire)) {
@@ -23,7 +23,7 @@ static nf_status launch_tap_kernel(long long total, int lds, const ConvPatchArgs
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
 }
 
-template <class Cfg>
+template <class Cfg, bool FUSED = false>
 static nf_status launch_tap(ConvPatchArgs& a, int B, hipStream_t s) {
   a.tiles_m = (a.cog + Cfg::kBM - 1) / Cfg::kBM;
   a.tiles_n = (a.HoWo + Cfg::kBN - 1) / Cfg::kBN;
@@ -34,7 +34,7 @@ static nf_status launch_tap(ConvPatchArgs& a, int B, hipStream_t s) {
   const int nt = (int)((tasks + 255) / 256);
   const int lds = Cfg::lds_bytes(a.PS);
   if (lds > 160 * 1024) return NF_EUNSUPPORTED;
-#define NF_TAP(VW_, NT_) return launch_tap_kernel<Cfg, VW_, NT_>(total, lds, a, s)
+#define NF_TAP(VW_, NT_) return launch_tap_kernel<Cfg, VW_, NT_, FUSED>(total, lds, a, s)
   switch (a.VW) {
     case 8: if (nt == 1) NF_TAP(8, 1); if (nt == 2) NF_TAP(8, 2); break;     // 32 staging registers per task
     case 4: if (nt == 1) NF_TAP(4, 1); if (nt == 2) NF_TAP(4, 2); if (nt == 3) NF_TAP(4, 3); break;
@@ -45,10 +45,23 @@ static nf_status launch_tap(ConvPatchArgs& a, int B, hipStream_t s) {
   return NF_EUNSUPPORTED;
 }
 
-// 3x3, dilation 1, one group per workgroup, cig % 32 == 0, 16-byte aligned x and w.  The caller has filled
-// everything but the tiling.  NF_EUNSUPPORTED = take another kernel.
+// 3x3, dilation 1, pad <= kLPad, (fused) groups of 32 k channels.  The caller has filled everything but the
+// tiling.  NF_EUNSUPPORTED = take another kernel.
 nf_status launch_conv_tap_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
-  if (a.S != 1 || a.cig % kTapCB != 0) return NF_EUNSUPPORTED;
+  if (a.cig % kTapCB != 0 || ((uintptr_t)a.x & 15) != 0) return NF_EUNSUPPORTED;
+  if (a.S > 1) {
+    // fused narrow groups: one 32-channel block, at most 32 rows; weight runs are read 16 or 8 bytes at a time
+    if (a.cig != kTapCB || a.cog > 32 || a.cig_real * a.S != kTapCB || a.cog_real * a.S != a.cog) return NF_EUNSUPPORTED;
+    if (((uintptr_t)a.w & (a.cig_real >= 8 ? 15 : 7)) != 0) return NF_EUNSUPPORTED;
+    ConvPatchArgs f = a;
+    if (a.stride == 1) {
+      const int rows = a.PS / a.PW;
+      f.PW = a.PW + ((a.Wo - a.PW) % 16 + 16) % 16;       // see below
+      f.PS = rows * f.PW;
+    }
+    return launch_tap<ConvTapCfg<32, 1, 4, 2>, true>(f, B, s);
+  }
+  if (((uintptr_t)a.w & 15) != 0) return NF_EUNSUPPORTED;
   static const int forced_bm = [] { const char* e = getenv("NETFUSE_TAP_BM"); return e ? atoi(e) : 0; }();
   const long long per_row_tile = (long long)((a.HoWo + 127) / 128) * a.nG * B;
   auto tiles = [&](int bm) { return per_row_tile * ((a.cog + bm - 1) / bm); };

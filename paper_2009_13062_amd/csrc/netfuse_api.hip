@@ -298,8 +298,11 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     const bool patch_ok = KH == 3 && KW == 3 && dilation == 1 && pad <= kLPad && aligned(x, 16) &&
                           ((S == 1 && cig % 16 == 0 && aligned(w, 16) && patch_tasks <= 12 * 256) ||
                            (S > 1 && 2 * patch_tasks <= 12 * 256));
-    if (!no_patch && patch_ok) {
-      // k x k: gather MFMA operands from an LDS copy of the zero-padded input patch (conv_patch.h)
+    // the tap-major kernel (conv_tap.h) checks its own task and LDS bounds
+    static const bool no_tap = getenv("NETFUSE_NO_TAP") != nullptr;
+    const bool tap_ok = !no_tap && KH == 3 && KW == 3 && dilation == 1 && pad <= kLPad && cig_e % 32 == 0;
+    if (!no_patch && (patch_ok || tap_ok)) {
+      // k x k: MFMA operands from an LDS copy of the zero-padded input patch (conv_tap.h, conv_patch.h)
       ConvPatchArgs c;
       memset(&c, 0, sizeof(c));
       c.x = (const bf16_t*)x; c.w = (const bf16_t*)w; c.R = (const bf16_t*)residual; c.y = (bf16_t*)y;
@@ -312,12 +315,11 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
       c.y_group = (long)cog_e * HoWo; c.y_image = (long)Ctot_out * HoWo;
       c.ep = a.ep;
       c.ep.row_vec_stride0 = cog_e;
-      static const bool no_tap = getenv("NETFUSE_NO_TAP") != nullptr;
-      if (!no_tap) {
+      if (tap_ok) {
         const nf_status st = launch_conv_tap_3x3(c, B, s);
         if (st != NF_EUNSUPPORTED) return st;
       }
-      return launch_conv_patch_3x3(c, B, s);
+      if (patch_ok) return launch_conv_patch_3x3(c, B, s);
     }
     a.geom.H = H; a.geom.W = W; a.geom.KH = KH; a.geom.KW = KW; a.geom.Wo = (int)Wo;
     a.geom.stride = stride; a.geom.pad = pad; a.geom.dil = dilation;
