@@ -84,8 +84,9 @@ int forced_dma() {
   return v;
 }
 
-// Direct-to-LDS kernel for a dense, fully aligned problem made of whole tiles, or -1.
-int pick_dma(int rows, int cols, int K, long long problems) {
+// Direct-to-LDS kernel for a dense, fully aligned problem made of whole tiles, or -1.  *cost_out receives the
+// cost of the choice in the model's unit (operand elements loaded by the busiest CU).
+int pick_dma(int rows, int cols, int K, long long problems, long long* cost_out = nullptr) {
   const int f = forced_dma();
   if (f == -1) return -1;
   auto fits = [&](int t) { return rows % kDmaBM[t] == 0 && cols % kDmaBN[t] == 0 && K % kDmaBK[t] == 0; };
@@ -107,6 +108,7 @@ int pick_dma(int rows, int cols, int K, long long problems) {
     if (kDmaBK[t] == 64) cost -= cost / 16;               // whole 128-byte lines of A per k-step: slightly cheaper than k32
     if (best < 0 || cost < best_cost) { best = t; best_cost = cost; }
   }
+  if (cost_out) *cost_out = best_cost;
   return best;
 }
 
@@ -183,8 +185,19 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     a.ep.act = act; a.ep.act_before_residual = 1;
     a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16);
     if (bkind == 8 && al == 16) {
-      const int d = pick_dma(N, Nout, K, M);
-      if (d >= 0) return launch_gemm_dma(d, L, s);
+      long long dma_cost = 0;
+      const int d = pick_dma(N, Nout, K, M, &dma_cost);
+      if (d >= 0) {
+        // Few merged models leave most CUs without a whole-tile workgroup; the 64x64 register-staged tile
+        // with its deep load pipeline then spreads the operand stream over more of them.  Same cost model,
+        // with the measured handicap of that kernel per byte (encoder layer at 8 models: the K = 3072
+        // matmul 25.6 -> 14.6 us, the 768 x 768 one 12.6 -> 11.0 us; at 32 models nothing changes).
+        const long long t64 = (long long)M * ((N + 63) / 64) * ((Nout + 63) / 64);
+        const long long reg_cost = (t64 + 255) / 256 * 128 * K;
+        if (forced_dma() == -2 && forced_tile() < 0 && K % 256 == 0 && reg_cost * 13 < dma_cost * 10)
+          return launch_gemm_any(bkind, al, T64x64, L, s);
+        return launch_gemm_dma(d, L, s);
+      }
     }
     return launch_gemm_any(bkind, al, pick_tile(N, Nout, M), L, s);
   }
