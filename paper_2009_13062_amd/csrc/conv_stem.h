@@ -80,28 +80,20 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(ConvStemArgs a) {
   for (int c = tid; c < (kLdsEls + CIN * a.PS) / 8; c += 256) lds_store16(As + c * 8, make_uint4(0, 0, 0, 0));
   __syncthreads();
 
-  // ---- weights: natural (co, ci, ky, kx) order in memory -> LDS column (ci*7 + ky)*8 + 1 + kx of row co
+  // ---- weights: natural (co, ci, ky, kx) order in memory -> LDS column (ci*7 + ky)*8 + 1 + kx of row co.
+  // Task = the 7 taps of one (co, ci, ky): contiguous in memory at element 7 * task (any 2-byte alignment),
+  // contiguous in LDS behind the zero slot; one division per task.
   {
-    const int nrows = min(rows_left, Cfg::kBM);
-    const int nel = nrows * CIN * KHW;
-    auto put = [&](int e, bf16_t v) {
-      const int co = e / (CIN * KHW), kn = e - co * (CIN * KHW);
-      const int r = kn / KW, kx = kn - r * KW;                      // r = ci*7 + ky
-      As[co * Cfg::kAPitch + r * 8 + 1 + kx] = v;
-    };
-    if (((uintptr_t)wg & 15) == 0) {
-      for (int c = tid; c * 8 < nel; c += 256) {
-        if (c * 8 + 8 <= nel) {
-          const uint4 v = *reinterpret_cast<const uint4*>(wg + c * 8);
-          const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+    const int ntask = min(rows_left, Cfg::kBM) * Cfg::kRows;
+    for (int task = tid; task < ntask; task += 256) {
+      const int co = task / Cfg::kRows, r = task - co * Cfg::kRows;      // r = ci*7 + ky
+      const bf16_t* src = wg + task * KW;
+      lds_bf16_t* dst = As + co * Cfg::kAPitch + r * 8 + 1;
+      bf16_t v[KW];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) put(c * 8 + e, (bf16_t)(w4[e / 2] >> (16 * (e % 2))));
-        } else {
-          for (int e = c * 8; e < nel; ++e) put(e, wg[e]);
-        }
-      }
-    } else {
-      for (int e = tid; e < nel; e += 256) put(e, wg[e]);
+      for (int kx = 0; kx < KW; ++kx) v[kx] = src[kx];
+#pragma unroll
+      for (int kx = 0; kx < KW; ++kx) dst[kx] = v[kx];
     }
   }
   // ---- patch: task = 8 pixels of one (channel, patch row), aligned on both sides
