@@ -29,7 +29,17 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_mfma_kernel(GemmArgs a) {
   const long cvo = z0 * a.ep.col_vec_stride0 + z1 * a.ep.col_vec_stride1 + col0;
   const bf16_t* Abase = a.A + z0 * a.sA0 + z1 * a.sA1 + (long)row0 * a.lda;
   const bf16_t* Bbase = a.B + z0 * a.sB0 + z1 * a.sB1;
-  if constexpr (BKIND == 0 || BKIND == 2 || BKIND == 21 || BKIND == 22 || BKIND == 24) {
+  if constexpr (BKIND == 0 || BKIND == 2 || BKIND == 21 || BKIND == 22 || BKIND == 24 || BKIND == 27) {
+    if constexpr (BKIND == 27 && Cfg::kDepth > 1 && ALIGN_A == 16) {
+      if (a.K % (kBK * Cfg::kDepth) == 0) {
+        ADeepLoader<Cfg::kBM, Cfg::kThreads> la;
+        la.init(Abase, a.lda, rows_left, threadIdx.x);
+        BRow7DeepLoader<Cfg::kBN, Cfg::kThreads> lb;
+        lb.init(Bbase, a.geom, a.cols / 7, threadIdx.x);
+        gemm_tile<Cfg, true>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
+        return;
+      }
+    }
     if constexpr ((BKIND == 21 || BKIND == 22 || BKIND == 24) && Cfg::kDepth > 1 && ALIGN_A == 16) {
       // whole k-step multiples stream through the deep pipeline
       if (a.K % (kBK * Cfg::kDepth) == 0) {
@@ -44,7 +54,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_mfma_kernel(GemmArgs a) {
     ATileLoader<Cfg::kBM, ALIGN_A, false, Cfg::kThreads> la;
     la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
     using Pairs = BStride2PairLoader<Cfg::kBN, BKIND == 24 ? 4 : 2, Cfg::kThreads>;
-    using Strided = typename std::conditional<BKIND == 2 || BKIND == 21, BStridedPointwiseLoader<Cfg::kBN, Cfg::kThreads>, Pairs>::type;
+    using Strided = typename std::conditional<BKIND == 2 || BKIND == 21 || BKIND == 27, BStridedPointwiseLoader<Cfg::kBN, Cfg::kThreads>, Pairs>::type;
     typename std::conditional<BKIND == 0, BIm2colLoader<Cfg::kBN, Cfg::kThreads>, Strided>::type lb;
     lb.xg = Bbase; lb.g = a.geom; lb.cols_left = cols_left; lb.K = a.K; lb.col0 = col0;
     gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
@@ -109,7 +119,7 @@ nf_status launch_gemm(GemmLaunch& L, hipStream_t s) {
 template <int ALIGN_A, int BKIND>
 nf_status launch_gemm_tile(int tile, GemmLaunch& L, hipStream_t s) {
   // depth of the load pipeline for the B kinds with branch-free loaders (the others keep one step in flight)
-  constexpr bool kDense = BKIND == 8 || BKIND == 1 || BKIND == 21 || BKIND == 22 || BKIND == 24;
+  constexpr bool kDense = BKIND == 8 || BKIND == 1 || BKIND == 21 || BKIND == 22 || BKIND == 24 || BKIND == 27;
   constexpr int D2 = kDense ? 2 : 1, D4 = kDense ? 4 : 1;
   switch (tile) {
     case T128x128: return launch_gemm<TileCfg<128, 128, 2, 2, D2>, ALIGN_A, BKIND>(L, s);

@@ -521,6 +521,58 @@ struct BPairDeepLoader {
   __device__ __forceinline__ void finish(lds_bf16_t*, int) const {}
 };
 
+// The same for 7 output columns (a 14-wide input: the last projection shortcut of a 224 x 224 ResNet), where
+// groups of 8 consecutive output positions would straddle rows and every position would cost its own load:
+// task = one (k row, output row): the 7 pixel pairs of input row 2 oy are contiguous (28 bytes at an 8-byte
+// aligned address: three 8-byte loads and one of 4), and their low halves go to LDS columns 7 oy .. 7 oy + 6
+// with 2-byte writes.  The whole image is one column tile (at most 8 output rows); LDS columns past the
+// image are never written and only feed output columns that are never stored.
+template <int BN, int NT>
+struct BRow7DeepLoader {
+  static constexpr int kPitch = BN + kPadB;
+  static constexpr int kWo = 7, kMaxHo = 8;
+  static constexpr int kPer = (kBK * kMaxHo + NT - 1) / NT;
+  static_assert(BN >= kWo * kMaxHo, "the image fits one column tile");
+  const uint32_t* planes;                // first input plane of this group and image, as pairs
+  int off[kPer];                         // pair offset of the task's input row at k = 0
+  int dst[kPer];                         // LDS element offset of its 7 columns, or -1: nothing to commit
+  int step;                              // pairs per k-step
+  struct Regs { uint32_t v[kPer][kWo]; };
+  __device__ __forceinline__ void init(const bf16_t* xg, const Im2colGeom& g, int Ho, int tid) {
+    planes = reinterpret_cast<const uint32_t*>(xg);
+    const int plane = g.H * g.W / 2;
+    step = kBK * plane;
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const int task = tid + t * NT;
+      const int krow = task / Ho, oy = task - krow * Ho;
+      const bool live = krow < kBK;
+      off[t] = live ? krow * plane + oy * g.W : 0;
+      dst[t] = live ? krow * kPitch + oy * kWo : -1;
+    }
+  }
+  __device__ __forceinline__ void fetch(Regs& regs, int k0, int) const {
+    const uint32_t* base = planes + (long)(k0 / kBK) * step;
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      const uint32_t* p = base + off[t];
+      const uint2 a = *reinterpret_cast<const uint2*>(p), b = *reinterpret_cast<const uint2*>(p + 2),
+                  c = *reinterpret_cast<const uint2*>(p + 4);
+      regs.v[t][0] = a.x; regs.v[t][1] = a.y; regs.v[t][2] = b.x; regs.v[t][3] = b.y;
+      regs.v[t][4] = c.x; regs.v[t][5] = c.y; regs.v[t][6] = p[6];
+    }
+  }
+  __device__ __forceinline__ void commit(const Regs& regs, lds_bf16_t* lds, int) const {
+#pragma unroll
+    for (int t = 0; t < kPer; ++t) {
+      if (dst[t] < 0) continue;
+#pragma unroll
+      for (int i = 0; i < kWo; ++i) lds[dst[t] + i] = (bf16_t)regs.v[t][i];
+    }
+  }
+  __device__ __forceinline__ void finish(lds_bf16_t*, int) const {}
+};
+
 // ------------------------------------------------------------------------------------------
 // The tile main loop and epilogue
 // ------------------------------------------------------------------------------------------

@@ -54,6 +54,7 @@ nf_status launch_gemm_any(int bkind, int align_a, int tile, GemmLaunch& L, hipSt
     case 24: return launch_gemm_bkind<24>(align_a, tile, L, s);
     case 22: return launch_gemm_bkind<22>(align_a, tile, L, s);
     case 21: return launch_gemm_bkind<21>(align_a, tile, L, s);
+    case 27: return launch_gemm_bkind<27>(align_a, tile, L, s);
     case 2: return launch_gemm_bkind<2>(align_a, tile, L, s);
     case 1: return launch_gemm_bkind<1>(align_a, tile, L, s);
     case 0: return launch_gemm_bkind<0>(align_a, tile, L, s);
@@ -344,6 +345,7 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
       if (stride == 2 && W == 2 * Wo) {
         if (Wo % 4 == 0 && plane % 8 == 0 && aligned(x, 16)) bkind = 24;
         else if (Wo % 2 == 0 && plane % 4 == 0 && aligned(x, 8)) bkind = 22;
+        else if (Wo == 7 && Ho <= 8 && plane % 4 == 0 && aligned(x, 8)) bkind = 27;
         else if (aligned(x, 4)) bkind = 21;
       }
     }
