@@ -138,6 +138,78 @@ __global__ __launch_bounds__(256) void layernorm_kernel(
   }
 }
 
+// The same for rows that fit in registers, ROWS consecutive rows of one model per wavefront (rows % ROWS
+// == 0): gamma and beta, 8 bytes per feature against 2 or 4 of the row itself, are fetched once per ROWS
+// rows instead of once per row, and the loads of all ROWS rows are in flight together.
+template <typename T, int VEC, int MAXIT, int ROWS>
+__global__ __launch_bounds__(256) void layernorm_rows_kernel(
+    const T* x, const T* residual, const float* __restrict__ gamma, const float* __restrict__ beta,
+    T* y, int M, int rows, int H, float eps, int channel_layout) {
+  const int lane = threadIdx.x % kWave;
+  const long wrow = ((long)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave) * ROWS;   // m*rows + r of the first row
+  if (wrow >= (long)M * rows) return;
+  const int m = (int)(wrow / rows), r0 = (int)(wrow % rows);
+  const float* gm = gamma + (size_t)m * H;
+  const float* bt = beta + (size_t)m * H;
+  size_t base[ROWS];
+#pragma unroll
+  for (int q = 0; q < ROWS; ++q)
+    base[q] = channel_layout ? ((size_t)(r0 + q) * M + m) * H : ((size_t)m * rows + r0 + q) * H;
+  float v[ROWS][MAXIT][VEC];
+  float sum[ROWS];
+#pragma unroll
+  for (int q = 0; q < ROWS; ++q) {
+    sum[q] = 0.f;
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it) {
+      const int i = (it * kWave + lane) * VEC;
+      if (i < H) {
+        VecIO<T, VEC>::load(x + base[q] + i, v[q][it]);
+        if (residual) {
+          float t[VEC];
+          VecIO<T, VEC>::load(residual + base[q] + i, t);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) v[q][it][e] += t[e];
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sum[q] += v[q][it][e];
+      }
+    }
+  }
+  float mean[ROWS], rstd[ROWS];
+#pragma unroll
+  for (int q = 0; q < ROWS; ++q) mean[q] = wave_sum(sum[q]) / (float)H;
+#pragma unroll
+  for (int q = 0; q < ROWS; ++q) {
+    float sq = 0.f;
+#pragma unroll
+    for (int it = 0; it < MAXIT; ++it) {
+      const int i = (it * kWave + lane) * VEC;
+      if (i < H) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { const float dlt = v[q][it][e] - mean[q]; sq = fmaf(dlt, dlt, sq); }
+      }
+    }
+    rstd[q] = 1.0f / sqrtf(wave_sum(sq) / (float)H + eps);
+  }
+#pragma unroll
+  for (int it = 0; it < MAXIT; ++it) {
+    const int i = (it * kWave + lane) * VEC;
+    if (i < H) {
+      float g[VEC], b[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { g[e] = gm[i + e]; b[e] = bt[i + e]; }
+#pragma unroll
+      for (int q = 0; q < ROWS; ++q) {
+        float o[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) o[e] = fmaf((v[q][it][e] - mean[q]) * rstd[q], g[e], b[e]);
+        VecIO<T, VEC>::store(y + base[q] + i, o);
+      }
+    }
+  }
+}
+
 // Merged inference batch norm (Section 3.1): per merged channel c of x[B][Ctot][HW].
 // One workgroup row per (b, c); gridDim.y splits long HW.
 template <typename T>

@@ -244,7 +244,7 @@ def test_linear_equals_pointwise_conv_on_gpu(nf):
 
 # ------------------------------------------------------------------ norms
 @pytest.mark.parametrize("dtype", DTYPES, ids=ids)
-@pytest.mark.parametrize("M,rows,H", [(8, 128, 768), (3, 5, 50), (2, 3, 3000), (2, 4, 1028), (32, 8, 64)])
+@pytest.mark.parametrize("M,rows,H", [(8, 128, 768), (3, 5, 50), (2, 3, 3000), (2, 4, 1028), (32, 8, 64), (32, 512, 64)])
 def test_layernorm_both_layouts(nf, oracle, M, rows, H, dtype):
     bf = dtype == torch.bfloat16
     x, r = grid(rnd(M, rows, H, std=2.0, mean=0.5), dtype), grid(rnd(M, rows, H), dtype)
