@@ -534,6 +534,16 @@ nf_status netfuse_avgpool_global(const void* x, void* y, int B, int Ctot, int HW
   const long long blocks = (nchan + 3) / 4;
   if (blocks > kMaxGrid) return NF_EUNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
+  if (HW <= 64) {
+    const unsigned blocks16 = (unsigned)((nchan + 15) / 16);
+    if (dt == NF_F32)
+      hipLaunchKernelGGL(avgpool_global_small_kernel<float>, dim3(blocks16), dim3(256), 0, s, (const float*)x,
+                         (float*)y, (size_t)nchan, HW);
+    else
+      hipLaunchKernelGGL(avgpool_global_small_kernel<bf16_t>, dim3(blocks16), dim3(256), 0, s, (const bf16_t*)x,
+                         (bf16_t*)y, (size_t)nchan, HW);
+    return launched();
+  }
   if (dt == NF_F32)
     hipLaunchKernelGGL(avgpool_global_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)x,
                        (float*)y, (size_t)nchan, HW);

@@ -321,6 +321,23 @@ __global__ __launch_bounds__(256) void avgpool_global_kernel(const T* __restrict
   if (lane == 0) store_f32(y + ch, s / (float)HW);
 }
 
+// The same for planes of at most 64 positions (the 7 x 7 output of a ResNet): 16 lanes per channel, 4
+// channels per wavefront, so a wavefront reads 4 * HW contiguous elements instead of HW.
+template <typename T>
+__global__ __launch_bounds__(256) void avgpool_global_small_kernel(const T* __restrict__ x, T* y, size_t nchan,
+                                                                   int HW) {
+  const int sub = threadIdx.x % 16;
+  const size_t ch = ((size_t)blockIdx.x * 256 + threadIdx.x) / 16;
+  float s = 0.f;
+  if (ch < nchan) {
+    const T* xc = x + ch * (size_t)HW;
+    for (int p = sub; p < HW; p += 16) s += load_f32(xc + p);
+  }
+#pragma unroll
+  for (int d = 8; d >= 1; d /= 2) s += __shfl_xor(s, d, 16);
+  if (sub == 0 && ch < nchan) store_f32(y + ch, s / (float)HW);
+}
+
 // Batch-merged [M][rows][H] <-> channel-merged [rows][M*H] (Section 3.2, Algorithm 1's reshape).
 // Index o runs over the destination, so writes are fully coalesced; reads are H-contiguous runs.
 template <typename T>
