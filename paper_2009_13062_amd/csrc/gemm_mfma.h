@@ -64,7 +64,8 @@ struct Epilogue {
   long col_vec_stride0, col_vec_stride1;
   int act;
   int act_before_residual;  // matmul: act(.) + residual;  convolution: act(. + residual)
-  int vec_store;            // C (and residual) rows are 16-byte aligned and cols % 8 == 0
+  int vec_store;            // 2: C (and residual) rows are 16-byte aligned and cols % 8 == 0; 1: 8-byte aligned
+                            // and cols % 4 == 0 (e.g. 14 x 14 planes); 0: element by element
 };
 
 // ------------------------------------------------------------------------------------------
@@ -602,7 +603,9 @@ __device__ __forceinline__ float act_const(float v) {
 }
 
 // ACT1: activation applied to the accumulator side (before the residual), ACT2: after the residual.
-template <class Cfg, int ACT1, int ACT2>
+// HALVES: the body for ep.vec_store == 1 (8-byte accesses, each half of an 8-column chunk whole or absent);
+// otherwise 16-byte accesses or, for ep.vec_store == 0, single elements.
+template <class Cfg, int ACT1, int ACT2, bool HALVES>
 __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::FN], lds_f32_t* const Es, bf16_t* C,
                                                   const bf16_t* R, long ldc, int rows_left, int cols_left,
                                                   const Epilogue& ep, long row_vec_off, long col_vec_off) {
@@ -673,7 +676,16 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
       live[t] = (kPassChunks % Cfg::kThreads == 0 || c < kPassChunks) && row < rows_left && col < cols_left;
       off[t] = (long)row * ldc + col;
       rr[t] = make_uint4(0, 0, 0, 0);
-      if (live[t] && R != nullptr && ep.vec_store) rr[t] = *reinterpret_cast<const uint4*>(R + off[t]);
+      if constexpr (HALVES) {
+        if (live[t] && R != nullptr) {
+          const uint2 lo = *reinterpret_cast<const uint2*>(R + off[t]);
+          uint2 hi = make_uint2(0, 0);
+          if (col + 4 < cols_left) hi = *reinterpret_cast<const uint2*>(R + off[t] + 4);
+          rr[t] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+      } else {
+        if (live[t] && R != nullptr && ep.vec_store) rr[t] = *reinterpret_cast<const uint4*>(R + off[t]);
+      }
     }
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
@@ -683,7 +695,7 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
       const lds_f32_t* src = Es + prow * kEP + col;
       const f32x4v_t v0 = *(const lds_f32x4_t*)src, v1 = *(const lds_f32x4_t*)(src + 4);
       float v[8] = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-      if (ep.vec_store) {
+      if (HALVES || ep.vec_store) {
         const uint32_t w[4] = {rr[t].x, rr[t].y, rr[t].z, rr[t].w};
         uint32_t o[4];
 #pragma unroll
@@ -692,7 +704,12 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
           const float a1 = act_const<ACT2>(v[2 * e + 1] + __uint_as_float(w[e] & 0xffff0000u));
           o[e] = pack_bf16x2(a0, a1);
         }
-        *reinterpret_cast<uint4*>(C + off[t]) = make_uint4(o[0], o[1], o[2], o[3]);
+        if constexpr (HALVES) {
+          *reinterpret_cast<uint2*>(C + off[t]) = make_uint2(o[0], o[1]);
+          if (col + 4 < cols_left) *reinterpret_cast<uint2*>(C + off[t] + 4) = make_uint2(o[2], o[3]);
+        } else {
+          *reinterpret_cast<uint4*>(C + off[t]) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
       } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -719,8 +736,13 @@ template <class Cfg>
 __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[Cfg::FM][Cfg::FN], lds_f32_t* const Es, bf16_t* C,
                                               const bf16_t* R, long ldc, int rows_left, int cols_left,
                                               const Epilogue& ep, long row_vec_off, long col_vec_off) {
-#define NF_EPI(A1, A2) \
-  gemm_epilogue_act<Cfg, A1, A2>(acc, Es, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off)
+#define NF_EPI(A1, A2)                                                                                          \
+  do {                                                                                                          \
+    if (ep.vec_store == 1)                                                                                      \
+      gemm_epilogue_act<Cfg, A1, A2, true>(acc, Es, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off); \
+    else                                                                                                        \
+      gemm_epilogue_act<Cfg, A1, A2, false>(acc, Es, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off); \
+  } while (0)
   if (ep.act == NF_ACT_NONE) NF_EPI(NF_ACT_NONE, NF_ACT_NONE);
   else if (ep.act_before_residual) {
     if (ep.act == NF_ACT_GELU) NF_EPI(NF_ACT_GELU, NF_ACT_NONE); else NF_EPI(NF_ACT_RELU, NF_ACT_NONE);

@@ -184,7 +184,8 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     L.nz1 = 1;
     a.ep.col_bias = bias; a.ep.col_vec_stride0 = Nout;
     a.ep.act = act; a.ep.act_before_residual = 1;
-    a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16);
+    a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16)  ? 2
+                     : Nout % 4 == 0 && aligned(Y, 8) && aligned(residual, 8) ? 1 : 0;
     if (bkind == 8 && al == 16) {
       long long dma_cost = 0;
       const int d = pick_dma(N, Nout, K, M, &dma_cost);
@@ -258,7 +259,8 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     a.ep.row_bias = bias; a.ep.row_scale = scale; a.ep.row_shift = shift;
     a.ep.row_vec_stride0 = cog; a.ep.row_vec_stride1 = 0;
     a.ep.act = act; a.ep.act_before_residual = 0;
-    a.ep.vec_store = HoWo % 8 == 0 && aligned(y, 16) && aligned(residual, 16);
+    a.ep.vec_store = HoWo % 8 == 0 && aligned(y, 16) && aligned(residual, 16)  ? 2
+                     : HoWo % 4 == 0 && aligned(y, 8) && aligned(residual, 8) ? 1 : 0;
     int al = common_align({w}, {Kdim});
     while (al > 2 && (Kdim % (al / 2)) != 0) al /= 2;
     const long long problems = (long long)M * g * B;
