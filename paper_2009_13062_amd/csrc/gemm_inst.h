@@ -10,7 +10,9 @@ namespace nf {
 
 template <class Cfg, int ALIGN_A, int BKIND>
 // 8-wave tiles are budgeted for two workgroups per CU: 4 wavefronts per SIMD, 128 registers per lane
-__global__ __launch_bounds__(Cfg::kThreads, Cfg::kThreads == 512 ? 4 : 1) void gemm_mfma_kernel(GemmArgs a) {
+// (the dense B kinds only: the gathering loaders would spill under that budget)
+__global__ __launch_bounds__(Cfg::kThreads, (Cfg::kThreads == 512 && (BKIND == 8 || BKIND == 1)) ? 4 : 1)
+void gemm_mfma_kernel(GemmArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   lds_bf16_t* smem = (lds_bf16_t*)smem_raw;
   unsigned id = xcd_remap(blockIdx.x, gridDim.x);
