@@ -152,6 +152,8 @@ CONV_CASES = [
     (2, 2, 128, 256, 1, 14, 14, 1, 1, 2, 0, 1),    # strided projection, Wo = 7: one input row per task, 8-wave tile
     (3, 1, 256, 64, 1, 14, 14, 1, 1, 2, 0, 1),     # the same on the 64x64 tile (two tasks per thread)
     (2, 1, 128, 256, 1, 10, 14, 1, 1, 2, 0, 1),    # the same with 5 output rows
+    (2, 1, 128, 256, 1, 10, 10, 1, 1, 2, 0, 1),    # strided projection, Wo = 5: one pixel pair per load through the deep pipeline
+    (2, 1, 128, 256, 1, 12, 12, 1, 1, 2, 0, 1),    # strided projection, Wo = 6: two pixel pairs per load through the deep pipeline
     (2, 1, 64, 128, 1, 15, 15, 1, 1, 2, 0, 1),     # strided projection, odd width
     (2, 1, 64, 64, 1, 12, 12, 1, 1, 3, 0, 1),      # pointwise, stride 3
     (2, 1, 64, 64, 1, 16, 16, 3, 3, 2, 1, 1),      # strided 3x3
