@@ -65,7 +65,8 @@ struct Epilogue {
   int act;
   int act_before_residual;  // matmul: act(.) + residual;  convolution: act(. + residual)
   int vec_store;            // 2: C (and residual) rows are 16-byte aligned and cols % 8 == 0; 1: 8-byte aligned
-                            // and cols % 4 == 0 (e.g. 14 x 14 planes); 0: element by element
+                            // and cols % 4 == 0 (e.g. 14 x 14 planes); 3: ldc == cols <= 64, so every tile spans
+                            // whole rows, and 32 rows start 16-byte aligned (e.g. 7 x 7 planes); 0: element by element
 };
 
 // ------------------------------------------------------------------------------------------
@@ -603,8 +604,8 @@ __device__ __forceinline__ float act_const(float v) {
 }
 
 // ACT1: activation applied to the accumulator side (before the residual), ACT2: after the residual.
-// HALVES: the body for ep.vec_store == 1 (8-byte accesses, each half of an 8-column chunk whole or absent);
-// otherwise 16-byte accesses or, for ep.vec_store == 0, single elements.
+// HALVES: the body for ep.vec_store == 1 (8-byte accesses, each half of an 8-column chunk whole or absent) and
+// == 3 (flat mode, see below); otherwise 16-byte accesses or, for ep.vec_store == 0, single elements.
 template <class Cfg, int ACT1, int ACT2, bool HALVES>
 __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::FN], lds_f32_t* const Es, bf16_t* C,
                                                   const bf16_t* R, long ldc, int rows_left, int cols_left,
@@ -664,6 +665,50 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
         }
     }
     __syncthreads();
+    if constexpr (HALVES) {
+      if (ep.vec_store == 3) {
+        // Flat mode: the tile spans whole rows (ldc == cols_left), so the 32 rows of each wave row are one
+        // contiguous, 16-byte aligned run of 32 * ldc elements in C and R; it is written 8 elements per
+        // thread regardless of where the rows begin (rows of 49 elements start at odd 2-byte addresses).
+        const int ld = (int)ldc;
+        const int cps = (32 * ld + 7) / 8;                         // chunks per run
+        for (int c = tid; c < Cfg::kWGM * cps; c += Cfg::kThreads) {
+          const int sp = c / cps, f0 = (c - sp * cps) * 8;
+          const int first = sp * Cfg::WM + i * 32;                   // first tile row of the run
+          const int n_el = max(0, min(32, rows_left - first)) * ld;
+          if (f0 >= n_el) continue;
+          int r = f0 / ld, col = f0 - r * ld;
+          float v[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            v[e] = f0 + e < n_el ? Es[(sp * 32 + r) * kEP + col] : 0.f;
+            if (++col == ld) { col = 0; ++r; }
+          }
+          const long o0 = (long)first * ldc + f0;
+          if (f0 + 8 <= n_el) {
+            uint4 w4 = make_uint4(0, 0, 0, 0);
+            if (R != nullptr) w4 = *reinterpret_cast<const uint4*>(R + o0);
+            const uint32_t w[4] = {w4.x, w4.y, w4.z, w4.w};
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float a0 = act_const<ACT2>(v[2 * e] + __uint_as_float(w[e] << 16));
+              const float a1 = act_const<ACT2>(v[2 * e + 1] + __uint_as_float(w[e] & 0xffff0000u));
+              o[e] = pack_bf16x2(a0, a1);
+            }
+            *reinterpret_cast<uint4*>(C + o0) = make_uint4(o[0], o[1], o[2], o[3]);
+          } else {
+            for (int e = 0; f0 + e < n_el; ++e) {
+              float x = v[e];
+              if (R) x += bf16_to_f32(R[o0 + e]);
+              C[o0 + e] = f32_to_bf16(act_const<ACT2>(x));
+            }
+          }
+        }
+        __syncthreads();
+        continue;
+      }
+    }
     // this thread's chunks of the pass: residual loads first (all in flight), then LDS -> bf16 -> HBM
     uint4 rr[kPer];
     long off[kPer];
@@ -738,7 +783,7 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[Cfg::FM][Cfg::FN],
                                               const Epilogue& ep, long row_vec_off, long col_vec_off) {
 #define NF_EPI(A1, A2)                                                                                          \
   do {                                                                                                          \
-    if (ep.vec_store == 1)                                                                                      \
+    if (ep.vec_store == 1 || ep.vec_store == 3)                                                                 \
       gemm_epilogue_act<Cfg, A1, A2, true>(acc, Es, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off); \
     else                                                                                                        \
       gemm_epilogue_act<Cfg, A1, A2, false>(acc, Es, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off); \

@@ -260,7 +260,8 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     a.ep.row_vec_stride0 = cog; a.ep.row_vec_stride1 = 0;
     a.ep.act = act; a.ep.act_before_residual = 0;
     a.ep.vec_store = HoWo % 8 == 0 && aligned(y, 16) && aligned(residual, 16)  ? 2
-                     : HoWo % 4 == 0 && aligned(y, 8) && aligned(residual, 8) ? 1 : 0;
+                     : HoWo % 4 == 0 && aligned(y, 8) && aligned(residual, 8) ? 1
+                     : HoWo <= 64 && ((long long)cog * HoWo) % 8 == 0 && aligned(y, 16) && aligned(residual, 16) ? 3 : 0;
     int al = common_align({w}, {Kdim});
     while (al > 2 && (Kdim % (al / 2)) != 0) al /= 2;
     const long long problems = (long long)M * g * B;
