@@ -69,7 +69,6 @@ nf_status launch_conv_stem(ConvStemArgs& a, int B, hipStream_t s) {
   const long long total = (long long)a.tiles_m * a.tiles_n * a.nG * B;
   if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
   if (a.PW % 8 != 0 || a.PS % 8 != 0 || a.PS % a.PW != 0) return NF_EUNSUPPORTED;
-  if (3LL * (a.PS / a.PW) * a.cpr > Cfg::kPatchTasksPerThread * 256) return NF_EUNSUPPORTED;
   const int lds = Cfg::lds_bytes(a.PS);
   if (lds > 64 * 1024) return NF_EUNSUPPORTED;
   hipLaunchKernelGGL((conv_stem_kernel<Cfg, 3>), dim3((unsigned)total), dim3(256), lds, s, a);

@@ -43,7 +43,6 @@ struct ConvStemCfg {
   static constexpr int kABytes = kBM * kAPitch * 2;
   static constexpr int kEpiPitch = kBN + 4;
   static constexpr int kLdsEpi = kWGM * 32 * kEpiPitch * (int)sizeof(float);
-  static constexpr int kPatchTasksPerThread = 6;          // 8-pixel chunk copies per thread (host checks)
   static constexpr int lds_bytes(int PS) {
     const int pipe = kABytes + CIN * PS * 2;
     return pipe > kLdsEpi ? pipe : kLdsEpi;
@@ -96,19 +95,20 @@ __global__ __launch_bounds__(256) void conv_stem_kernel(ConvStemArgs a) {
       for (int kx = 0; kx < KW; ++kx) dst[kx] = v[kx];
     }
   }
-  // ---- patch: task = 8 pixels of one (channel, patch row), aligned on both sides
+  // ---- patch: 8-pixel chunks, aligned on both sides.  32 lanes run along a patch row (chunk index), the 8
+  // lane groups of the workgroup take 8 rows at a time: no division anywhere (row -> (channel, patch row) by
+  // comparison, CIN being tiny).
   {
-    const int ntasks = CIN * PH * a.cpr;
+    const int nrows = CIN * PH;
+    for (int row = tid / 32; row < nrows; row += 8) {
+      int ci = 0;
 #pragma unroll
-    for (int u = 0; u < Cfg::kPatchTasksPerThread; ++u) {
-      const int task = tid + u * 256;
-      const int row = task / a.cpr, ch = task - row * a.cpr;
-      const int ci = row / PH, py = row - ci * PH;
-      const int iy = iy0 + py;
-      if (task < ntasks && iy >= 0 && iy < a.H) {
-        const uint4 v = *reinterpret_cast<const uint4*>(xg + ((long)ci * a.H + iy) * a.W + ch * 8);
-        lds_store16(Ps + ci * a.PS + py * a.PW + Cfg::kColPad + ch * 8, v);
-      }
+      for (int c = 1; c < CIN; ++c) ci += row >= c * PH;
+      const int py = row - ci * PH, iy = iy0 + py;
+      if (iy < 0 || iy >= a.H) continue;
+      const bf16_t* src = xg + ((long)ci * a.H + iy) * a.W;
+      lds_bf16_t* dst = Ps + ci * a.PS + py * a.PW + Cfg::kColPad;
+      for (int ch = tid % 32; ch < a.cpr; ch += 32) lds_store16(dst + ch * 8, *reinterpret_cast<const uint4*>(src + ch * 8));
     }
   }
   __syncthreads();
