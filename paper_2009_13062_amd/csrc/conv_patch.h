@@ -53,6 +53,7 @@ struct ConvPatchCfg {
   static constexpr int WM = BM / WGM, WN = kBN / WGN, FM = WM / 32, FN = WN / 32;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
   static constexpr int kKHW = KH * KW, kCB = CB, kKH = KH, kKW = KW;
+  static constexpr bool kRowConsts = true;
   static constexpr int kStageK = CB * kKHW;            // k extent of one stage
   static constexpr int kHalfK = kStageK / 2;           // per lane half
   static_assert(kHalfK % 8 == 0, "each half must be a whole number of 8-k slots");

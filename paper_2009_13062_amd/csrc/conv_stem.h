@@ -35,6 +35,7 @@ struct ConvStemCfg {
   static constexpr int kKH = 7, kKW = 7, kStride = 2, kPad = 3, kColPad = 8;
   static constexpr int kBM = 64, kBN = 128, kWGM = 1, kWGN = 4, kThreads = 256;
   static constexpr int WM = 64, WN = 32, FM = 2, FN = 1;
+  static constexpr bool kRowConsts = true;
   static constexpr int kRows = CIN * kKH;                 // (ci, ky) rows of the k dimension
   static constexpr int kSteps = (kRows + 1) / 2;          // MFMA steps of 16 k: two rows each
   static constexpr int kK = kSteps * 16;                  // padded k extent in LDS

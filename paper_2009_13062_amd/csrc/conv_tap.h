@@ -37,6 +37,7 @@ struct ConvTapCfg {
   static constexpr int WM = BM / WGM, WN = kBN / WGN, FM = WM / 32, FN = WN / 32;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
   static constexpr int kTaps = 9;
+  static constexpr bool kRowConsts = true;
   static constexpr int kAPitch = kTaps * kTapCB + 8;     // elements; (pitch / 8) odd -> 16-byte slots rotate
   static_assert((kAPitch / 8) % 2 == 1, "A pitch must rotate bank groups");
   static constexpr int kABytes = BM * kAPitch * 2;

@@ -30,6 +30,7 @@ struct DmaCfg {
   static_assert(BK == 32 || BK == 64, "k-step of 32 or 64");
   static constexpr int kBM = BM, kBN = BN, kBK = BK, kWGM = WGM, kWGN = WGN, kNS = NS;
   static constexpr int kNW = WGM * WGN, kThreads = kNW * kWave;
+  static constexpr bool kRowConsts = false;              // matmul epilogues carry per-column constants only
   static constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
   static constexpr int kARow = BK * 2, kBRow = BN * 2;                 // bytes per LDS row

@@ -584,6 +584,7 @@ struct TileCfg {
   static_assert(WGM * WGN == 4 || WGM * WGN == 8, "4 or 8 wavefronts per workgroup");
   static constexpr int kBM = BM, kBN = BN, kWGM = WGM, kWGN = WGN;
   static constexpr int kThreads = WGM * WGN * kWave;
+  static constexpr bool kRowConsts = true;               // convolution epilogues carry per-row scale/shift
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int FM = WM / 32, FN = WN / 32;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile is made of 32x32 MFMA blocks");
@@ -644,14 +645,33 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
         }
   }
 
+  // per-row constants of this lane for every pass, fetched together: one memory round trip instead of one
+  // per pass (short-K layers are a chain of such round trips).  Configurations whose callers never pass row
+  // constants (Cfg::kRowConsts == false: the whole-tile matmul kernels) keep the per-pass form, which costs
+  // them nothing and leaves their register allocation alone.
+  float rbs[FM], rss[FM], rts[FM];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    rbs[i] = 0.f; rss[i] = 1.f; rts[i] = 0.f;
+    if constexpr (Cfg::kRowConsts) {
+      const int row = wm * Cfg::WM + i * 32 + l32;           // this lane's row in the tile
+      if (row < rows_left) {
+        if (ep.row_bias) rbs[i] = ep.row_bias[row_vec_off + row];
+        if (ep.row_scale) { rss[i] = ep.row_scale[row_vec_off + row]; rts[i] = ep.row_shift[row_vec_off + row]; }
+      }
+    }
+  }
+
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
     {
-      const int row = wm * Cfg::WM + i * 32 + l32;           // this lane's row in the tile
-      float rb = 0.f, rs = 1.f, rt = 0.f;
-      if (row < rows_left) {
-        if (ep.row_bias) rb = ep.row_bias[row_vec_off + row];
-        if (ep.row_scale) { rs = ep.row_scale[row_vec_off + row]; rt = ep.row_shift[row_vec_off + row]; }
+      float rb = rbs[i], rs = rss[i], rt = rts[i];
+      if constexpr (!Cfg::kRowConsts) {
+        const int row = wm * Cfg::WM + i * 32 + l32;
+        if (row < rows_left) {
+          if (ep.row_bias) rb = ep.row_bias[row_vec_off + row];
+          if (ep.row_scale) { rs = ep.row_scale[row_vec_off + row]; rt = ep.row_shift[row_vec_off + row]; }
+        }
       }
       lds_f32_t* erow = Es + (wm * 32 + l32) * kEP + wn * Cfg::WN + half * 4;
 #pragma unroll
