@@ -11,8 +11,11 @@
  *
  * Conventions for every entry point
  *   - All pointers are DEVICE pointers on the current HIP device, owned by the caller, who
- *     keeps them alive until `stream` has passed the call.  The library allocates nothing and
- *     keeps no mutable global state; calls may be made from any thread.
+ *     keeps them alive until `stream` has passed the call.  The library allocates nothing; calls
+ *     may be made from any thread.  The only state it keeps is (a) one flag per kernel that needs
+ *     more than 64 KB of LDS, set when its first launch has opted in to that size (idempotent),
+ *     and (b) the calling thread's pending request of netfuse_time_next_launch.  It reads no
+ *     environment variable.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call validates
  *     its arguments on the host BEFORE touching HIP, enqueues its kernels and returns; it
  *     never synchronises.  Kernels use no atomics and no hidden workspace: results are
@@ -54,6 +57,30 @@ typedef enum { NF_MERGE_BATCH = 0, NF_MERGE_CHANNEL = 1 } nf_merge_dim;
 nf_status netfuse_linear(const void* X, const void* W, const float* bias, const void* residual,
                          void* Y, int M, int N, int K, int Nout, nf_dtype dt, nf_act act,
                          void* stream);
+
+/*
+ * The same merged matmul on weights re-laid out once, offline (Section 3.1, "Matrix multiplication":
+ * the M weight matrices are concatenated once when the models are merged; at inference they are
+ * static and are nearly all of the bytes a forward pass reads).
+ *
+ * Packed layout, for a panel width `panel` (a multiple of 32 that divides Nout; K a multiple of 32):
+ *   Wp[m][p][kb][j][r][c] = W[m][32 kb + r][panel p + 32 j + c]      0 <= r, c < 32,
+ *   p < Nout/panel, kb < K/32, j < panel/32  -- i.e. 2 KB blocks of 32 k x 32 n, the blocks of one
+ *   k-block of a panel contiguous, then the next k-block, then the next panel, then the next model.
+ *   Same element count as W.  bf16 only (NF_EUNSUPPORTED for float).
+ * netfuse_linear_packed_panel: the panel width the kernel chosen for (M, N, K, Nout) streams as one
+ *   contiguous run per workgroup, or 0 if this shape has no packed kernel (then use
+ *   netfuse_linear).  Any multiple of it that divides Nout is accepted by the other two calls.
+ * netfuse_linear_pack_weight: W[M][K][Nout] -> Wp; W and Wp must not overlap; 16-byte aligned.
+ * netfuse_linear_packed: Y[m] = act(X[m] . W[m] + bias[m]) + residual[m] as netfuse_linear, bit for
+ *   bit the same result; NF_EUNSUPPORTED if N, K, Nout are not whole tiles of a packed kernel.
+ */
+int netfuse_linear_packed_panel(int M, int N, int K, int Nout, nf_dtype dt);
+nf_status netfuse_linear_pack_weight(const void* W, void* Wp, int M, int K, int Nout, int panel,
+                                     nf_dtype dt, void* stream);
+nf_status netfuse_linear_packed(const void* X, const void* Wp, const float* bias, const void* residual,
+                                void* Y, int M, int N, int K, int Nout, int panel, nf_dtype dt,
+                                nf_act act, void* stream);
 
 /*
  * Merged convolution = grouped convolution with M*g groups (Section 3.1, "Convolution" and
@@ -138,6 +165,17 @@ nf_status netfuse_avgpool_global(const void* x, void* y, int B, int Ctot, int HW
  */
 nf_status netfuse_merge_transpose(const void* src, void* dst, int M, int rows, int H, int to_channel,
                                   nf_dtype dt, void* stream);
+
+/*
+ * Measurement hook (Section 5.1 times every configuration; this makes the per-kernel figures exact):
+ * arms the calling thread so that the NEXT kernel this library launches from this thread records its
+ * own begin and end timestamps on the device into the two HIP events (hipEvent_t passed as void*,
+ * created by the caller with timing enabled; either may be NULL).  hipEventElapsedTime(start, stop)
+ * then is that kernel's duration as a kernel trace would report it, without the host-side cost of an
+ * event pair.  The request is consumed by one launch; passing two NULLs cancels it.  Not for use
+ * under stream capture.
+ */
+nf_status netfuse_time_next_launch(void* start_event, void* stop_event);
 
 /* Static description of a status code; never NULL. */
 const char* netfuse_strerror(nf_status status);

@@ -26,7 +26,8 @@ MERGE_BATCH, MERGE_CHANNEL = 0, 1
 
 EXPORTS = ("netfuse_linear", "netfuse_conv2d", "netfuse_layernorm", "netfuse_batchnorm",
            "netfuse_bn_fold", "netfuse_attention", "netfuse_maxpool2d", "netfuse_avgpool_global",
-           "netfuse_merge_transpose", "netfuse_strerror")
+           "netfuse_merge_transpose", "netfuse_linear_pack_weight", "netfuse_linear_packed",
+           "netfuse_time_next_launch", "netfuse_linear_packed_panel", "netfuse_strerror")
 
 
 class NetFuseError(RuntimeError):
@@ -51,6 +52,10 @@ def _load() -> ctypes.CDLL:
     lib.netfuse_maxpool2d.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp]
     lib.netfuse_avgpool_global.argtypes = [vp, vp, i, i, i, i, vp]
     lib.netfuse_merge_transpose.argtypes = [vp, vp, i, i, i, i, i, vp]
+    lib.netfuse_linear_packed_panel.argtypes = [i, i, i, i, i]
+    lib.netfuse_linear_pack_weight.argtypes = [vp, vp, i, i, i, i, i, vp]
+    lib.netfuse_linear_packed.argtypes = [vp, vp, fp, vp, vp, i, i, i, i, i, i, i, vp]
+    lib.netfuse_time_next_launch.argtypes = [vp, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.netfuse_strerror.argtypes = [ctypes.c_int]
@@ -106,6 +111,38 @@ def linear(X, W, bias=None, residual=None, act=ACT_NONE, out=None, stream=None):
         _ptr(X), _ptr(W, X), _ptr(bias, f32=True), _ptr(residual, X), _ptr(Y, X), M, N, K, Nout,
         _dt(X), int(act), _stream(stream)))
     return Y
+
+
+def linear_packed_panel(M, N, K, Nout, dtype=torch.bfloat16) -> int:
+    """Panel width to pack W[M,K,Nout] with for N rows per model; 0 = no packed kernel for this shape."""
+    return int(lib.netfuse_linear_packed_panel(M, N, K, Nout, NF_BF16 if dtype == torch.bfloat16 else NF_F32))
+
+
+def linear_pack_weight(W, panel, out=None, stream=None):
+    """W[M,K,Nout] -> block-packed copy (same shape and dtype, layout of include/netfuse.h)."""
+    M, K, Nout = W.shape
+    Wp = torch.empty_like(W) if out is None else out
+    _check("netfuse_linear_pack_weight", lib.netfuse_linear_pack_weight(
+        _ptr(W), _ptr(Wp, W), M, K, Nout, int(panel), _dt(W), _stream(stream)))
+    return Wp
+
+
+def linear_packed(X, Wp, panel, bias=None, residual=None, act=ACT_NONE, out=None, stream=None):
+    """netfuse_linear on weights packed by linear_pack_weight(W, panel); Wp keeps W's shape [M,K,Nout]."""
+    M, N, K = X.shape
+    Nout = Wp.shape[2]
+    if Wp.shape[0] != M or Wp.shape[1] != K:
+        raise ValueError("Wp must be [M, K, Nout]")
+    Y = torch.empty((M, N, Nout), dtype=X.dtype, device=X.device) if out is None else out
+    _check("netfuse_linear_packed", lib.netfuse_linear_packed(
+        _ptr(X), _ptr(Wp, X), _ptr(bias, f32=True), _ptr(residual, X), _ptr(Y, X), M, N, K, Nout,
+        int(panel), _dt(X), int(act), _stream(stream)))
+    return Y
+
+
+def time_next_launch(start_event, stop_event):
+    """Arm the next kernel launch of this thread with two raw hipEvent_t handles (ints or None)."""
+    _check("netfuse_time_next_launch", lib.netfuse_time_next_launch(start_event, stop_event))
 
 
 def conv_out_size(n, k, stride, pad, dil=1):

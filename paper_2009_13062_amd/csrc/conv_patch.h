@@ -18,8 +18,10 @@
 // Narrow groups (ResNeXt: 4, 8 or 16 channels per group): S = 32 / cig consecutive groups are fused
 // into one 32-channel block whose weight tile is block diagonal (row r of the tile carries the cig*KHW
 // weights of its own group at column offset (r / cog)*cig*KHW, zeros elsewhere).  The MFMA then
-// multiplies S times more zeros than data, which is free next to the HBM traffic of such layers, and
-// no product ever crosses a group: group isolation is exact, not approximate.
+// multiplies S times more zeros than data, which is free next to the HBM traffic of such layers.  For
+// finite inputs the zero blocks contribute exactly 0; a NaN or infinity in one group's input would
+// still reach its S - 1 neighbours through 0 * NaN, so the caller fuses groups of ONE model only
+// (g % S == 0): isolation BETWEEN MODELS is exact for any input values.
 //
 // One workgroup = one (image, group, 128-position tile, BM output channels).  Accumulators and the
 // fused epilogue (folded batch norm scale/shift, residual, ReLU) are those of gemm_mfma.h.

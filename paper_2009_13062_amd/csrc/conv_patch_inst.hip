@@ -19,7 +19,7 @@ static nf_status launch_kernel(long long total, int lds, const ConvPatchArgs& a,
       opted_in.store(true, std::memory_order_release);
     }
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(256), lds, s, a);
+  nf_launch(kern, dim3((unsigned)total), dim3(256), lds, s, a);
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
 }
 
@@ -71,7 +71,7 @@ nf_status launch_conv_stem(ConvStemArgs& a, int B, hipStream_t s) {
   if (a.PW % 8 != 0 || a.PS % 8 != 0 || a.PS % a.PW != 0) return NF_EUNSUPPORTED;
   const int lds = Cfg::lds_bytes(a.PS);
   if (lds > 64 * 1024) return NF_EUNSUPPORTED;
-  hipLaunchKernelGGL((conv_stem_kernel<Cfg, 3>), dim3((unsigned)total), dim3(256), lds, s, a);
+  nf_launch((conv_stem_kernel<Cfg, 3>), dim3((unsigned)total), dim3(256), lds, s, a);
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
 }
 

@@ -19,7 +19,7 @@ static nf_status launch_tap_kernel(long long total, int lds, const ConvPatchArgs
       opted_in.store(true, std::memory_order_release);
     }
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(256), lds, s, a);
+  nf_launch(kern, dim3((unsigned)total), dim3(256), lds, s, a);
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
 }
 
@@ -62,7 +62,7 @@ nf_status launch_conv_tap_3x3(ConvPatchArgs& a, int B, hipStream_t s) {
     return launch_tap<ConvTapCfg<32, 1, 4, 2>, true>(f, B, s);
   }
   if (((uintptr_t)a.w & 15) != 0) return NF_EUNSUPPORTED;
-  static const int forced_bm = [] { const char* e = getenv("NETFUSE_TAP_BM"); return e ? atoi(e) : 0; }();
+  static const int forced_bm = [] { const char* e = dev_getenv("NETFUSE_TAP_BM"); return e ? atoi(e) : 0; }();
   const long long per_row_tile = (long long)((a.HoWo + 127) / 128) * a.nG * B;
   auto tiles = [&](int bm) { return per_row_tile * ((a.cog + bm - 1) / bm); };
   // measured on the 3x3 layers of ResNet-50 at 32 merged models: a taller row tile copies the input patch

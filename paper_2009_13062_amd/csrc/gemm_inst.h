@@ -115,7 +115,7 @@ nf_status launch_gemm(GemmLaunch& L, hipStream_t s) {
       opted_in.store(true, std::memory_order_release);
     }
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(Cfg::kThreads), Cfg::kLdsBytes, s, a);
+  nf_launch(kern, dim3((unsigned)total), dim3(Cfg::kThreads), Cfg::kLdsBytes, s, a);
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
 }
 
@@ -125,8 +125,6 @@ nf_status launch_gemm_tile(int tile, GemmLaunch& L, hipStream_t s) {
   constexpr bool kDense = BKIND == 8 || BKIND == 1 || BKIND == 21 || BKIND == 22 || BKIND == 24 || BKIND == 27;
   constexpr int D2 = kDense ? 2 : 1, D4 = kDense ? 4 : 1;
   switch (tile) {
-    case T128x128: return launch_gemm<TileCfg<128, 128, 2, 2, D2>, ALIGN_A, BKIND>(L, s);
-    case T64x128: return launch_gemm<TileCfg<64, 128, 2, 2, D2>, ALIGN_A, BKIND>(L, s);
     case T64x64: return launch_gemm<TileCfg<64, 64, 2, 2, D4>, ALIGN_A, BKIND>(L, s);
     case T32x128: return launch_gemm<TileCfg<32, 128, 1, 4, D2>, ALIGN_A, BKIND>(L, s);
     case T128x128w8: return launch_gemm<TileCfg<128, 128, 2, 4, D2>, ALIGN_A, BKIND>(L, s);

@@ -6,6 +6,7 @@
 #include <limits.h>
 
 #include "gemm_mfma.h"
+#include "nf_launch.h"
 
 namespace nf {
 
@@ -15,6 +16,7 @@ struct GemmArgs {
   long lda, ldb, ldc;
   long sA0, sA1, sB0, sB1, sC0, sC1;      // strides of the two batch coordinates (elements)
   int rows, cols, K, nz0, tiles_m, tiles_n;
+  int panel;                               // block-packed B (netfuse_linear_pack_weight): columns per panel, else 0
   Epilogue ep;
   Im2colGeom geom;                         // implicit-B convolution only
 };
@@ -24,9 +26,9 @@ struct GemmLaunch {
   int nz1;
 };
 
-enum TileId { T128x128 = 0, T64x128, T64x64, T32x128, T128x128w8, kNumTiles };
-constexpr int kTileBM[kNumTiles] = {128, 64, 64, 32, 128};
-constexpr int kTileBN[kNumTiles] = {128, 128, 64, 128, 128};
+enum TileId { T64x64 = 0, T32x128, T128x128w8, kNumTiles };
+constexpr int kTileBM[kNumTiles] = {64, 32, 128};
+constexpr int kTileBN[kNumTiles] = {64, 128, 128};
 
 // Direct-to-LDS pipelined kernels for problems made of whole tiles (BM x BN, k-step, stages).
 enum DmaTileId { D256x256k32s4 = 0, D128x128k32s4, D128x128k64s3w8, D128x384k32s4w12, D128x288k32s4w12, D128x96k64s4w12, kNumDmaTiles };
@@ -35,6 +37,16 @@ constexpr int kDmaBN[kNumDmaTiles] = {256, 128, 128, 384, 288, 96};
 constexpr int kDmaBK[kNumDmaTiles] = {32, 32, 64, 32, 32, 64};
 // dense, 16-byte aligned A and B; NF_EUNSUPPORTED if the problem is not a whole number of tiles
 nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s);
+// the same kernels reading a block-packed B operand (L.a.panel columns per panel, a multiple of the tile width)
+nf_status launch_gemm_dma_packed(int cfg, GemmLaunch& L, hipStream_t s);
+
+// Streaming kernels (gemm_stream.h): nsub consecutive column tiles per workgroup through one load pipeline,
+// register epilogue.  Whole-tile problems with 8-byte aligned output rows; NF_EUNSUPPORTED otherwise.
+enum StreamTileId { S128x96k64 = 0, S128x128k32, S128x288k32, S128x384k32, S256x256k32, S256x128k32, kNumStreamTiles };
+constexpr int kStreamBM[kNumStreamTiles] = {128, 128, 128, 128, 256, 256};
+constexpr int kStreamBN[kNumStreamTiles] = {96, 128, 288, 384, 256, 128};
+constexpr int kStreamBK[kNumStreamTiles] = {64, 32, 32, 32, 32, 32};
+nf_status launch_gemm_stream(int cfg, int nsub, bool packed, GemmLaunch& L, hipStream_t s);
 
 // BKIND: 8 / 4 / 1 = dense B read with that vector width; 0 = implicit (im2col) B.
 // align_a: 16, 8, 4 or 2 = byte alignment of every A row start (and K a multiple of align_a/2).

@@ -1,0 +1,198 @@
+// Streaming form of the direct-to-LDS bf16 MFMA contraction (gemm_dma.h) for the merged matmul: one
+// workgroup computes NSUB consecutive column tiles of one (problem, row tile) through ONE continuous load
+// pipeline, and each tile's epilogue runs out of registers while the next tile's operands are already
+// landing in LDS.
+//
+// Why: measured on MI355X, a weight-streaming matmul (128 rows per model) spends a quarter to a third of
+// its time in the epilogue of its single tile per compute unit -- bias, GELU and the bf16 conversion are
+// 60-80 VALU clocks per element with nothing else in flight, and the staging of the accumulators through
+// LDS adds four workgroup barriers -- while the same operand stream without any epilogue runs at the rate of
+// a plain read kernel (6 TB/s).  Here
+//   * the epilogue touches no LDS and no barrier: a lane owns 4 consecutive columns of a row (the
+//     accumulators are computed transposed), so it loads 8 bytes of residual, converts and stores 8 bytes;
+//     32 lanes x 2 halves write 32 rows x 16 bytes per instruction and four such instructions complete
+//     64 contiguous bytes per row, which the L2 merges before they reach HBM;
+//   * the load pipeline never drains between the tiles of a workgroup: the stage counter runs over
+//     NSUB x K/BK steps, the source pointers jump to the next tile after a tile's last k-step, so
+//     NS-1 stages of the NEXT tile are in flight during an epilogue, and every wave starts the next tile
+//     as soon as it is done with its own part of the epilogue;
+//   * the A operand (the model's activation rows) is re-read per column tile, from L2.
+// Bit-for-bit the same result as the other contraction kernels: same k order, same epilogue arithmetic.
+#pragma once
+#include "gemm_dma.h"
+
+namespace nf {
+
+// Epilogue of one whole BM x BN tile straight from the accumulators (layout: see gemm_mfma.h).
+// Needs 8-byte aligned rows of C and R (ldc % 4 == 0) and a 16-byte aligned column-constant vector.
+template <class Cfg, int ACT>
+__device__ __forceinline__ void stream_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::FN], bf16_t* C, const bf16_t* R,
+                                                    long ldc, const float* col_bias) {
+  constexpr int FM = Cfg::FM, FN = Cfg::FN;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
+  const int half = lane / 32, l32 = lane % 32;
+#pragma unroll
+  for (int j = 0; j < FN; ++j) {
+    const int col0 = wn * Cfg::WN + j * 32 + half * 4;
+    float4 cb[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      cb[q] = col_bias ? *reinterpret_cast<const float4*>(col_bias + col0 + q * 8) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+      const long off = (long)(wm * Cfg::WM + i * 32 + l32) * ldc + col0;
+      uint2 rr[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        rr[q] = R ? *reinterpret_cast<const uint2*>(R + off + q * 8) : make_uint2(0u, 0u);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float b[4] = {cb[q].x, cb[q].y, cb[q].z, cb[q].w};
+        const uint32_t w[2] = {rr[q].x, rr[q].y};
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = act_const<ACT>(fmaf(acc[i][j][q * 4 + e] + b[e] + 0.f, 1.f, 0.f));
+        const float o0 = v[0] + __uint_as_float(w[0] << 16), o1 = v[1] + __uint_as_float(w[0] & 0xffff0000u);
+        const float o2 = v[2] + __uint_as_float(w[1] << 16), o3 = v[3] + __uint_as_float(w[1] & 0xffff0000u);
+        *reinterpret_cast<uint2*>(C + off + q * 8) = make_uint2(pack_bf16x2(o0, o1), pack_bf16x2(o2, o3));
+      }
+    }
+  }
+}
+
+// A, B, C, R, col_bias point at the workgroup's first tile; consecutive tiles are b_tile_stride elements
+// apart in B and Cfg::kBN columns apart in C, R and col_bias.  act is applied before the residual.
+template <class Cfg, bool PACKED>
+__device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, long lda, const bf16_t* __restrict__ B,
+                                                  long ldb, long b_tile_stride, int K, int nsub, lds_u8_t* smem,
+                                                  bf16_t* C, const bf16_t* R, long ldc, const float* col_bias,
+                                                  int act) {
+  constexpr int FM = Cfg::FM, FN = Cfg::FN, NS = Cfg::kNS, BK = Cfg::kBK;
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
+  const int half = lane / 32, l32 = lane % 32, l16 = lane % 16;
+  const int nk = K / BK;
+
+  // ---- what this lane fetches (as gemm_dma_tile), plus the pointer jump after a tile's last k-step
+  const bf16_t* src[Cfg::kMaxPer];
+  long inc[Cfg::kMaxPer], jump[Cfg::kMaxPer];
+#pragma unroll
+  for (int t = 0; t < Cfg::kMaxPer; ++t) {
+    const int blk = t * Cfg::kNW + wave;
+    if (blk < Cfg::kABlocks) {
+      const int row = blk * Cfg::kARpi + lane / Cfg::kACpr;
+      const int c = (lane % Cfg::kACpr) ^ Cfg::swz_a(row);
+      src[t] = A + (long)row * lda + c * 8;
+      inc[t] = BK;
+      jump[t] = -(long)(nk - 1) * BK;                        // back to k = 0 of the same rows
+    } else if constexpr (PACKED) {
+      constexpr int kHalves = Cfg::kBN / 16;
+      const int hb = blk - Cfg::kABlocks;
+      src[t] = B + (long)(hb / kHalves) * ldb + (hb % kHalves) * 512 + lane * 8;
+      inc[t] = (long)(BK / 32) * ldb;
+      jump[t] = b_tile_stride - (long)(nk - 1) * inc[t];
+    } else {
+      const int flat = (blk - Cfg::kABlocks) * 64 + lane;
+      const int krow = flat / Cfg::kBCpr;
+      const int c = (flat % Cfg::kBCpr) ^ (Cfg::kBSwz * (krow % 4));
+      src[t] = B + (long)krow * ldb + c * 8;
+      inc[t] = (long)BK * ldb;
+      jump[t] = b_tile_stride - (long)(nk - 1) * inc[t];
+    }
+  }
+  const bool extra = Cfg::kRem == 0 || wave < Cfg::kRem;
+  int kt_issue = 0;                                          // k-step, within its tile, of the next stage to issue
+  auto issue_stage = [&](int g) {
+    lds_u8_t* stage = smem + (g % NS) * Cfg::kStageBytes;
+    const bool last = kt_issue == nk - 1;
+#pragma unroll
+    for (int t = 0; t < Cfg::kMaxPer; ++t) {
+      if (t + 1 < Cfg::kMaxPer || extra)
+        __builtin_amdgcn_global_load_lds((glb_u8_t*)src[t], stage + (t * Cfg::kNW + wave) * 1024, 16, 0, 0);
+      src[t] += last ? jump[t] : inc[t];
+    }
+    kt_issue = last ? 0 : kt_issue + 1;
+  };
+  // Stage g has landed once at most the loads of the NS-2 younger stages are pending.  Memory operations of
+  // a wave retire in issue order, so the epilogue's own loads and stores, which are younger than the stages
+  // in flight at that time, only make this fixed threshold more conservative.
+  auto wait_landed = [&]() {
+    if (extra) wait_vmcnt<(NS - 2) * Cfg::kMaxPer>(); else wait_vmcnt<(NS - 2) * (Cfg::kMaxPer - 1)>();
+  };
+
+  int a_off[FM], b_off[FN][2];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) a_off[i] = (wm * Cfg::WM + i * 32 + l32) * Cfg::kARow;
+  const int a_swz = Cfg::swz_a(l32);
+#pragma unroll
+  for (int j = 0; j < FN; ++j)
+#pragma unroll
+    for (int hl = 0; hl < 2; ++hl) {
+      const int kr = 8 * half + l16 / 4 + 4 * hl;
+      const int n = wn * Cfg::WN + j * 32 + ((lane / 16) % 2) * 16 + (l16 % 4) * 4;
+      if constexpr (PACKED)
+        b_off[j][hl] = Cfg::kABytes + (n / 32) * 2048 + kr * 64 + (n % 32) * 2;
+      else
+        b_off[j][hl] = Cfg::kABytes + kr * Cfg::kBRow + (((n / 8) ^ (Cfg::kBSwz * (l16 / 4))) * 16) + ((n / 4) % 2) * 8;
+    }
+  auto b_step = [](int kk) {
+    return PACKED ? (kk / 2) * (Cfg::kBN / 32) * 2048 + (kk % 2) * 16 * 64 : kk * 16 * Cfg::kBRow;
+  };
+
+  const int total = nsub * nk;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < total) issue_stage(s);
+
+  int g = 0;
+  for (int sub = 0; sub < nsub; ++sub) {
+    f32x16_t acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    for (int kt = 0; kt < nk; ++kt, ++g) {
+      if (g + NS - 2 < total) wait_landed(); else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      const lds_u8_t* stage = smem + (g % NS) * Cfg::kStageBytes;
+      bf16x8_t af[BK / 16][FM], bfr[BK / 16][FN];
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+          af[kk][i] = *(const lds_bf16x8_t*)(stage + a_off[i] + (((2 * kk + half) ^ a_swz) * 16));
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][0] + b_step(kk)));
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][1] + b_step(kk)));
+          const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          bfr[kk][j] = __builtin_bit_cast(bf16x8_t, both);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      wait_lgkmcnt0();
+      __builtin_amdgcn_sched_barrier(0);
+      if (g + NS - 1 < total) issue_stage(g + NS - 1);      // refills the stage read in step g-1
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kk = 0; kk < BK / 16; ++kk)
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+          for (int j = 0; j < FN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+    }
+    const long c0 = (long)sub * Cfg::kBN;
+    const float* cb = col_bias ? col_bias + c0 : nullptr;
+    const bf16_t* Rt = R ? R + c0 : nullptr;
+    if (act == NF_ACT_GELU) stream_epilogue_act<Cfg, NF_ACT_GELU>(acc, C + c0, Rt, ldc, cb);
+    else if (act == NF_ACT_RELU) stream_epilogue_act<Cfg, NF_ACT_RELU>(acc, C + c0, Rt, ldc, cb);
+    else stream_epilogue_act<Cfg, NF_ACT_NONE>(acc, C + c0, Rt, ldc, cb);
+  }
+}
+
+}  // namespace nf

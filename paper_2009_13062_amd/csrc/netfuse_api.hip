@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -17,6 +18,7 @@
 #include "generic_kernels.h"
 #include "nf_common.h"
 #include "norm_kernels.h"
+#include "pack_kernels.h"
 
 using namespace nf;
 
@@ -38,6 +40,17 @@ inline long long prod(std::initializer_list<long long> v) {
 }
 constexpr long long kMaxElems = (1LL << 62);     // element counts must stay below this
 constexpr long long kMaxGrid = 0x7fffffffLL;
+
+}  // namespace
+
+namespace nf {
+LaunchTiming& launch_timing() {
+  static thread_local LaunchTiming t = {nullptr, nullptr};
+  return t;
+}
+}  // namespace nf
+
+namespace {
 
 inline nf_status launched() { return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH; }
 
@@ -65,7 +78,7 @@ nf_status launch_gemm_any(int bkind, int align_a, int tile, GemmLaunch& L, hipSt
 // Optional override for tile-shape sweeps: NETFUSE_TILE=<index into TileId>, read once.
 int forced_tile() {
   static const int v = [] {
-    const char* e = getenv("NETFUSE_TILE");
+    const char* e = dev_getenv("NETFUSE_TILE");
     if (!e || !*e) return -1;
     const int t = atoi(e);
     return (t >= 0 && t < kNumTiles) ? t : -1;
@@ -77,7 +90,7 @@ int forced_tile() {
 // to disable them.
 int forced_dma() {
   static const int v = [] {
-    const char* e = getenv("NETFUSE_DMA");
+    const char* e = dev_getenv("NETFUSE_DMA");
     if (!e || !*e) return -2;
     const int t = atoi(e);
     return (t >= -1 && t < kNumDmaTiles) ? t : -2;
@@ -113,6 +126,55 @@ int pick_dma(int rows, int cols, int K, long long problems, long long* cost_out 
   return best;
 }
 
+// pick_dma(), unless the register-staged 64x64 tile is expected to be faster (kPreferSmallTile).
+// Few merged models leave most CUs without a whole-tile workgroup; the 64x64 register-staged tile
+// with its deep load pipeline then spreads the operand stream over more of them.  Same cost model,
+// with the measured handicap of that kernel per byte (encoder layer at 8 models: the K = 3072
+// matmul 25.6 -> 14.6 us, the 768 x 768 one 12.6 -> 11.0 us; at 32 models nothing changes).
+constexpr int kPreferSmallTile = -2;
+int pick_dma_or_small(int N, int Nout, int K, long long M) {
+  long long dma_cost = 0;
+  const int d = pick_dma(N, Nout, K, M, &dma_cost);
+  if (d < 0) return -1;
+  const long long t64 = M * ((N + 63) / 64) * ((Nout + 63) / 64);
+  const long long reg_cost = (t64 + 255) / 256 * 128 * K;
+  if (forced_dma() == -2 && forced_tile() < 0 && K % 256 == 0 && reg_cost * 13 < dma_cost * 10) return kPreferSmallTile;
+  return d;
+}
+
+// Streaming kernel (gemm_stream.h) for a problem that pick_dma() routed to direct-to-LDS tile d, or -1.
+// Measured on MI355X, 32 models (us, register epilogue / LDS-staged epilogue of the same tile):
+//   GELU epilogues, 128 rows: 768 -> 3072  37.8 / 39.4;   512 rows, three 256x256 tiles per workgroup through
+//   one pipeline: 105.6 / 119.1.  The barrier-free epilogue pays where the epilogue is VALU heavy; plain
+//   bias / residual epilogues are as fast or faster through LDS (full-line stores), so they keep it --
+//   except that 512-row problems whose 256x256 tiling leaves a quarter of the last round of workgroups
+//   empty (768 -> 2304: 576 tiles) run as three 128x384 tiles per workgroup (82.7 / 88.4).
+int pick_stream(int d, int N, int Nout, int K, long long M, int act, int* nsub) {
+  *nsub = 1;
+  if (d == D256x256k32s4) {
+    const long long tiles = M * (N / 256) * (Nout / 256);
+    if (act == NF_ACT_GELU) {
+      if (tiles >= 3 * 256 && (Nout / 256) % 3 == 0) *nsub = 3;
+      return S256x256k32;
+    }
+    if (tiles % 256 != 0 && N % 128 == 0 && Nout % 384 == 0 && (Nout / 384) % 3 == 0) {
+      const long long t384 = M * (N / 128) * (Nout / 384);
+      if (t384 % (3 * 256) == 0) { *nsub = 3; return S128x384k32; }
+    }
+    return -1;
+  }
+  if (d == D128x384k32s4w12 && act == NF_ACT_GELU) return S128x384k32;
+  return -1;
+}
+
+// Developer override NETFUSE_STREAM="<StreamTileId>,<nsub>" (read at every call in builds with developer
+// switches): force a streaming kernel and its number of column tiles per workgroup.
+bool forced_stream(int* cfg, int* nsub) {
+  const char* e = dev_getenv("NETFUSE_STREAM");
+  if (!e || !*e) return false;
+  return sscanf(e, "%d,%d", cfg, nsub) == 2 && *cfg >= 0 && *cfg < kNumStreamTiles && *nsub >= 1;
+}
+
 // Tile choice for the register-staged kernels.
 int pick_tile(int rows, int cols, long long problems) {
   const int f = forced_tile();
@@ -142,6 +204,13 @@ int common_align(std::initializer_list<const void*> ptrs, std::initializer_list<
 
 // ==========================================================================================
 extern "C" {
+
+nf_status netfuse_time_next_launch(void* start_event, void* stop_event) {
+  LaunchTiming& t = launch_timing();
+  t.start = (hipEvent_t)start_event;
+  t.stop = (hipEvent_t)stop_event;
+  return NF_OK;
+}
 
 const char* netfuse_strerror(nf_status st) {
   switch (st) {
@@ -187,17 +256,19 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16)  ? 2
                      : Nout % 4 == 0 && aligned(Y, 8) && aligned(residual, 8) ? 1 : 0;
     if (bkind == 8 && al == 16) {
-      long long dma_cost = 0;
-      const int d = pick_dma(N, Nout, K, M, &dma_cost);
+      int scfg, snsub;
+      if (forced_stream(&scfg, &snsub)) {
+        const nf_status st = launch_gemm_stream(scfg, snsub, false, L, s);
+        if (st != NF_EUNSUPPORTED) return st;
+      }
+      const int d = pick_dma_or_small(N, Nout, K, M);
+      if (d == kPreferSmallTile) return launch_gemm_any(bkind, al, T64x64, L, s);
       if (d >= 0) {
-        // Few merged models leave most CUs without a whole-tile workgroup; the 64x64 register-staged tile
-        // with its deep load pipeline then spreads the operand stream over more of them.  Same cost model,
-        // with the measured handicap of that kernel per byte (encoder layer at 8 models: the K = 3072
-        // matmul 25.6 -> 14.6 us, the 768 x 768 one 12.6 -> 11.0 us; at 32 models nothing changes).
-        const long long t64 = (long long)M * ((N + 63) / 64) * ((Nout + 63) / 64);
-        const long long reg_cost = (t64 + 255) / 256 * 128 * K;
-        if (forced_dma() == -2 && forced_tile() < 0 && K % 256 == 0 && reg_cost * 13 < dma_cost * 10)
-          return launch_gemm_any(bkind, al, T64x64, L, s);
+        const int sc = pick_stream(d, N, Nout, K, M, act, &snsub);
+        if (sc >= 0) {
+          const nf_status st = launch_gemm_stream(sc, snsub, false, L, s);
+          if (st != NF_EUNSUPPORTED) return st;
+        }
         return launch_gemm_dma(d, L, s);
       }
     }
@@ -206,10 +277,89 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
   const int tiles_m = (N + 63) / 64, tiles_n = (Nout + 63) / 64;
   const long long total = prod({tiles_m, tiles_n, M});
   if (total > kMaxGrid) return NF_EUNSUPPORTED;
-  hipLaunchKernelGGL(linear_generic_kernel<float>, dim3((unsigned)total), dim3(256), 0, s, (const float*)X,
+  nf_launch(linear_generic_kernel<float>, dim3((unsigned)total), dim3(256), 0, s, (const float*)X,
                      (const float*)W, bias, (const float*)residual, (float*)Y, N, K, Nout, (int)act, tiles_m,
                      tiles_n);
   return launched();
+}
+
+int netfuse_linear_packed_panel(int M, int N, int K, int Nout, nf_dtype dt) {
+  if (dt != NF_BF16 || M <= 0 || N <= 0 || K <= 0 || Nout <= 0 || K % 32 != 0 || Nout % 32 != 0) return 0;
+  const int d = pick_dma_or_small(N, Nout, K, M);
+  if (d < 0) return 0;
+  int nsub;
+  const int sc = pick_stream(d, N, Nout, K, M, NF_ACT_NONE, &nsub);      // the activation is not known here
+  return sc >= 0 ? kStreamBN[sc] : kDmaBN[d];
+}
+
+nf_status netfuse_linear_pack_weight(const void* W, void* Wp, int M, int K, int Nout, int panel, nf_dtype dt,
+                                     void* stream) {
+  if (!W || !Wp || W == Wp) return NF_EINVAL;
+  if (M <= 0 || K <= 0 || Nout <= 0 || panel <= 0 || !is_dtype(dt)) return NF_EINVAL;
+  if (K % 32 != 0 || panel % 32 != 0 || Nout % panel != 0) return NF_EINVAL;
+  const long long total = prod({M, K, Nout});
+  if (total >= kMaxElems) return NF_EINVAL;
+  if (dt != NF_BF16) return NF_EUNSUPPORTED;
+  if (!aligned(W, 16) || !aligned(Wp, 16)) return NF_EINVAL;
+  const long long chunks = total / 8, blocks = (chunks + 255) / 256;
+  if (blocks > kMaxGrid) return NF_EUNSUPPORTED;
+  nf_launch(pack_weight_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const bf16_t*)W,
+            (bf16_t*)Wp, K, Nout, panel, (size_t)chunks);
+  return launched();
+}
+
+nf_status netfuse_linear_packed(const void* X, const void* Wp, const float* bias, const void* residual, void* Y,
+                                int M, int N, int K, int Nout, int panel, nf_dtype dt, nf_act act, void* stream) {
+  if (!X || !Wp || !Y) return NF_EINVAL;
+  if (M <= 0 || N <= 0 || K <= 0 || Nout <= 0 || panel <= 0) return NF_EINVAL;
+  if (!is_dtype(dt) || !is_act(act)) return NF_EINVAL;
+  if (K % 32 != 0 || panel % 32 != 0 || Nout % panel != 0) return NF_EINVAL;
+  if (prod({M, N, K}) >= kMaxElems || prod({M, K, Nout}) >= kMaxElems || prod({M, N, Nout}) >= kMaxElems)
+    return NF_EINVAL;
+  if (dt != NF_BF16) return NF_EUNSUPPORTED;
+  if (!aligned(X, 2) || !aligned(Wp, 16) || !aligned(Y, 2) || !aligned(residual, 2) || !aligned(bias, 4))
+    return NF_EINVAL;
+  if (!aligned(X, 16) || K % 8 != 0) return NF_EUNSUPPORTED;
+  // the widest direct-to-LDS tile of this shape class whose width divides the panel
+  int d = pick_dma_or_small(N, Nout, K, M);
+  if (d == kPreferSmallTile) d = pick_dma(N, Nout, K, M);
+  if (d < 0 || panel % kDmaBN[d] != 0) {
+    d = -1;
+    long long best = 0;
+    for (int t = 0; t < kNumDmaTiles; ++t) {
+      if (N % kDmaBM[t] || Nout % kDmaBN[t] || K % kDmaBK[t] || panel % kDmaBN[t]) continue;
+      const long long tiles = (long long)M * (N / kDmaBM[t]) * (Nout / kDmaBN[t]);
+      const long long cost = (tiles + 255) / 256 * ((long long)kDmaBM[t] + kDmaBN[t]) * K;
+      if (d < 0 || cost < best) { d = t; best = cost; }
+    }
+    if (d < 0) return NF_EUNSUPPORTED;
+  }
+  GemmLaunch L;
+  memset(&L, 0, sizeof(L));
+  GemmArgs& a = L.a;
+  a.A = (const bf16_t*)X; a.B = (const bf16_t*)Wp; a.R = (const bf16_t*)residual; a.C = (bf16_t*)Y;
+  a.B_end = a.B + (long long)M * K * Nout;
+  a.lda = K; a.ldb = 0; a.ldc = Nout; a.panel = panel;
+  a.sA0 = (long)N * K; a.sB0 = (long)K * Nout; a.sC0 = (long)N * Nout;
+  a.rows = N; a.cols = Nout; a.K = K; a.nz0 = M;
+  L.nz1 = 1;
+  a.ep.col_bias = bias; a.ep.col_vec_stride0 = Nout;
+  a.ep.act = act; a.ep.act_before_residual = 1;
+  a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16) ? 2
+                   : Nout % 4 == 0 && aligned(Y, 8) && aligned(residual, 8) ? 1 : 0;
+  int scfg, snsub;
+  if (forced_stream(&scfg, &snsub)) {
+    const nf_status st = launch_gemm_stream(scfg, snsub, true, L, (hipStream_t)stream);
+    if (st != NF_EUNSUPPORTED) return st;
+  }
+  {
+    const int sc = pick_stream(d, N, Nout, K, M, act, &snsub);
+    if (sc >= 0 && panel % kStreamBN[sc] == 0) {
+      const nf_status st = launch_gemm_stream(sc, snsub, true, L, (hipStream_t)stream);
+      if (st != NF_EUNSUPPORTED) return st;
+    }
+  }
+  return launch_gemm_dma_packed(d, L, (hipStream_t)stream);
 }
 
 nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const float* scale, const float* shift,
@@ -243,7 +393,7 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
   const int HoWo = (int)(Ho * Wo);
   const int Kdim = cig * KH * KW;
 
-  static const bool no_mfma_conv = getenv("NETFUSE_CONV_GENERIC") != nullptr;
+  static const bool no_mfma_conv = dev_getenv("NETFUSE_CONV_GENERIC") != nullptr;
   if (dt == NF_BF16 && !no_mfma_conv) {
     GemmLaunch L;
     memset(&L, 0, sizeof(L));
@@ -279,7 +429,7 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
       if (al_b == 16 && HoWo % 8 == 0) bkind = 8;
       return launch_gemm_any(bkind, al, tile, L, s);
     }
-    static const bool no_patch = getenv("NETFUSE_NO_PATCH") != nullptr;
+    static const bool no_patch = dev_getenv("NETFUSE_NO_PATCH") != nullptr;
     if (!no_patch && KH == 7 && KW == 7 && stride == 2 && pad == 3 && dilation == 1 && cig == 3 && W % 8 == 0 &&
         aligned(x, 16)) {
       // the ResNet stem: a few input channels under a wide kernel (conv_stem.h)
@@ -305,9 +455,12 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     const int PWp = (maxcol + 1 + 7) / 8 * 8;
     const int span = (int)std::min<long long>(Ho, (126 + Wo) / Wo + 1);
     const int PHmax = (span - 1) * stride + KH;
-    // narrow groups: fuse S = 32 / cig consecutive groups into one 32-channel block (block-diagonal weights)
+    // narrow groups: fuse S = 32 / cig consecutive groups OF ONE MODEL into one 32-channel block
+    // (block-diagonal weights).  The zero blocks are still multiplied with the neighbouring groups'
+    // activations, and 0 * NaN = NaN, so a fused block never spans two models (g % S == 0): a non-finite
+    // value in one model's input cannot reach another model's output.
     int S = 1;
-    if (cig < 32 && 32 % cig == 0 && cig % 4 == 0 && (long long)(32 / cig) * cog <= 32 && (M * g) % (32 / cig) == 0 &&
+    if (cig < 32 && 32 % cig == 0 && cig % 4 == 0 && (long long)(32 / cig) * cog <= 32 && g % (32 / cig) == 0 &&
         aligned(w, 8))
       S = 32 / cig;
     const int cig_e = S * cig, cog_e = S * cog;               // channels of the (fused) group a workgroup handles
@@ -316,7 +469,7 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
                           ((S == 1 && cig % 16 == 0 && aligned(w, 16) && patch_tasks <= 12 * 256) ||
                            (S > 1 && 2 * patch_tasks <= 12 * 256));
     // the tap-major kernel (conv_tap.h) checks its own task and LDS bounds
-    static const bool no_tap = getenv("NETFUSE_NO_TAP") != nullptr;
+    static const bool no_tap = dev_getenv("NETFUSE_NO_TAP") != nullptr;
     const bool tap_ok = !no_tap && KH == 3 && KW == 3 && dilation == 1 && pad <= kLPad && cig_e % 32 == 0;
     if (!no_patch && (patch_ok || tap_ok)) {
       // k x k: MFMA operands from an LDS copy of the zero-padded input patch (conv_tap.h, conv_patch.h)
@@ -336,7 +489,10 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
         const nf_status st = launch_conv_tap_3x3(c, B, s);
         if (st != NF_EUNSUPPORTED) return st;
       }
-      if (patch_ok) return launch_conv_patch_3x3(c, B, s);
+      if (patch_ok) {
+        const nf_status st = launch_conv_patch_3x3(c, B, s);
+        if (st != NF_EUNSUPPORTED) return st;           // else: the implicit-GEMM kernel below takes any shape
+      }
     }
     a.geom.H = H; a.geom.W = W; a.geom.KH = KH; a.geom.KW = KW; a.geom.Wo = (int)Wo;
     a.geom.stride = stride; a.geom.pad = pad; a.geom.dil = dilation;
@@ -361,11 +517,11 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
   geo.stride = stride; geo.pad = pad; geo.dil = dilation;
   const unsigned grid = grid_for(n_out, 256);
   if (dt == NF_F32)
-    hipLaunchKernelGGL(conv2d_generic_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x,
+    nf_launch(conv2d_generic_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x,
                        (const float*)w, bias, scale, shift, (const float*)residual, (float*)y, geo, (int)act,
                        (size_t)n_out);
   else
-    hipLaunchKernelGGL(conv2d_generic_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)x,
+    nf_launch(conv2d_generic_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)x,
                        (const bf16_t*)w, bias, scale, shift, (const bf16_t*)residual, (bf16_t*)y, geo, (int)act,
                        (size_t)n_out);
   return launched();
@@ -392,12 +548,12 @@ nf_status netfuse_layernorm(const void* x, const void* residual, const float* ga
   // rows that fit in registers: two per wavefront (they share the model's gamma and beta) once there are
   // enough rows to keep every CU busy that way (measured: 16384 rows of 768 11.8 -> 10.4 us, 4096 rows
   // 3.9 -> 4.7 us)
-  static const int ln_forced = [] { const char* e = getenv("NETFUSE_LN_ROWS"); return e ? atoi(e) : 0; }();
+  static const int ln_forced = [] { const char* e = dev_getenv("NETFUSE_LN_ROWS"); return e ? atoi(e) : 0; }();
   const int ln_rows = ln_forced ? ln_forced : (nrows >= 16384 ? 2 : 1);
   if (vec && H <= kWave * 4 * 4 && (ln_rows == 2 || ln_rows == 4) && rows % ln_rows == 0) {
     const long long blocks_r = (nrows / ln_rows + 3) / 4;
 #define NF_LNR(T, R)                                                                                      \
-  hipLaunchKernelGGL((layernorm_rows_kernel<T, 4, 4, R>), dim3((unsigned)blocks_r), dim3(256), 0, s,       \
+  nf_launch((layernorm_rows_kernel<T, 4, 4, R>), dim3((unsigned)blocks_r), dim3(256), 0, s,       \
                      (const T*)x, (const T*)residual, gamma, beta, (T*)y, M, rows, H, eps, ch)
     if (dt == NF_F32) { if (ln_rows == 2) NF_LNR(float, 2); else NF_LNR(float, 4); }
     else { if (ln_rows == 2) NF_LNR(bf16_t, 2); else NF_LNR(bf16_t, 4); }
@@ -405,7 +561,7 @@ nf_status netfuse_layernorm(const void* x, const void* residual, const float* ga
     return launched();
   }
 #define NF_LN(T, VEC, MAXIT)                                                                             \
-  hipLaunchKernelGGL((layernorm_kernel<T, VEC, MAXIT>), dim3((unsigned)blocks), dim3(256), 0, s,         \
+  nf_launch((layernorm_kernel<T, VEC, MAXIT>), dim3((unsigned)blocks), dim3(256), 0, s,         \
                      (const T*)x, (const T*)residual, gamma, beta, (T*)y, M, rows, H, eps, ch)
   if (dt == NF_F32) {
     if (vec) NF_LN(float, 4, 4); else NF_LN(float, 1, 8);
@@ -434,10 +590,10 @@ nf_status netfuse_batchnorm(const void* x, const float* gamma, const float* beta
   hipStream_t s = (hipStream_t)stream;
   const unsigned gy = (unsigned)((HW + 1023) / 1024 > 64 ? 64 : (HW + 1023) / 1024);
   if (dt == NF_F32)
-    hipLaunchKernelGGL(batchnorm_kernel<float>, dim3((unsigned)rowsbc, gy), dim3(256), 0, s, (const float*)x,
+    nf_launch(batchnorm_kernel<float>, dim3((unsigned)rowsbc, gy), dim3(256), 0, s, (const float*)x,
                        gamma, beta, mean, var, (const float*)residual, (float*)y, (int)Ctot, HW, eps, (int)act);
   else
-    hipLaunchKernelGGL(batchnorm_kernel<bf16_t>, dim3((unsigned)rowsbc, gy), dim3(256), 0, s, (const bf16_t*)x,
+    nf_launch(batchnorm_kernel<bf16_t>, dim3((unsigned)rowsbc, gy), dim3(256), 0, s, (const bf16_t*)x,
                        gamma, beta, mean, var, (const bf16_t*)residual, (bf16_t*)y, (int)Ctot, HW, eps, (int)act);
   return launched();
 }
@@ -449,7 +605,7 @@ nf_status netfuse_bn_fold(const float* gamma, const float* beta, const float* me
   if (!aligned(gamma, 4) || !aligned(beta, 4) || !aligned(mean, 4) || !aligned(var, 4) || !aligned(scale, 4) ||
       !aligned(shift, 4))
     return NF_EINVAL;
-  hipLaunchKernelGGL(bn_fold_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, gamma,
+  nf_launch(bn_fold_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, gamma,
                      beta, mean, var, scale, shift, n, eps);
   return launched();
 }
@@ -480,7 +636,7 @@ nf_status netfuse_attention(const void* Q, const void* K, const void* V, const f
     const int qblocks = (S + 127) / 128;
     const long long total = prod({M, B, heads, qblocks});
     if (total > kMaxGrid) return NF_EUNSUPPORTED;
-    hipLaunchKernelGGL(attention_mfma_d64_kernel, dim3((unsigned)total), dim3(256), 0, s, a, qblocks);
+    nf_launch(attention_mfma_d64_kernel, dim3((unsigned)total), dim3(256), 0, s, a, qblocks);
     return launched();
   }
   if (d > 256) return NF_EUNSUPPORTED;
@@ -489,7 +645,7 @@ nf_status netfuse_attention(const void* Q, const void* K, const void* V, const f
   if (blocks > kMaxGrid) return NF_EUNSUPPORTED;
   const int dpl = (d + 63) / 64;
 #define NF_ATT(T, DPL) \
-  hipLaunchKernelGGL((attention_generic_kernel<T, DPL>), dim3((unsigned)blocks), dim3(256), 0, s, a)
+  nf_launch((attention_generic_kernel<T, DPL>), dim3((unsigned)blocks), dim3(256), 0, s, a)
   if (dt == NF_F32) {
     if (dpl == 1) NF_ATT(float, 1); else if (dpl == 2) NF_ATT(float, 2); else NF_ATT(float, 4);
   } else {
@@ -513,16 +669,16 @@ nf_status netfuse_maxpool2d(const void* x, void* y, int B, int Ctot, int H, int 
   hipStream_t s = (hipStream_t)stream;
   if (dt == NF_BF16 && k == 3 && stride == 2 && pad == 1 && W % 8 == 0 && aligned(x, 16) && aligned(y, 8)) {
     // Wo = W / 2 is a multiple of 4: four outputs per thread from 16-byte loads
-    hipLaunchKernelGGL(maxpool3x3s2_bf16_kernel, dim3(grid_for(n_out / 4, 256)), dim3(256), 0, s, (const bf16_t*)x,
+    nf_launch(maxpool3x3s2_bf16_kernel, dim3(grid_for(n_out / 4, 256)), dim3(256), 0, s, (const bf16_t*)x,
                        (bf16_t*)y, H, W, Ho, Wo, (size_t)(n_out / 4));
     return launched();
   }
   const unsigned grid = grid_for(n_out, 256);
   if (dt == NF_F32)
-    hipLaunchKernelGGL(maxpool2d_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x, (float*)y, H, W, Ho,
+    nf_launch(maxpool2d_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x, (float*)y, H, W, Ho,
                        Wo, k, stride, pad, (size_t)n_out);
   else
-    hipLaunchKernelGGL(maxpool2d_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, H, W,
+    nf_launch(maxpool2d_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)x, (bf16_t*)y, H, W,
                        Ho, Wo, k, stride, pad, (size_t)n_out);
   return launched();
 }
@@ -540,18 +696,18 @@ nf_status netfuse_avgpool_global(const void* x, void* y, int B, int Ctot, int HW
   if (HW <= 64) {
     const unsigned blocks16 = (unsigned)((nchan + 15) / 16);
     if (dt == NF_F32)
-      hipLaunchKernelGGL(avgpool_global_small_kernel<float>, dim3(blocks16), dim3(256), 0, s, (const float*)x,
+      nf_launch(avgpool_global_small_kernel<float>, dim3(blocks16), dim3(256), 0, s, (const float*)x,
                          (float*)y, (size_t)nchan, HW);
     else
-      hipLaunchKernelGGL(avgpool_global_small_kernel<bf16_t>, dim3(blocks16), dim3(256), 0, s, (const bf16_t*)x,
+      nf_launch(avgpool_global_small_kernel<bf16_t>, dim3(blocks16), dim3(256), 0, s, (const bf16_t*)x,
                          (bf16_t*)y, (size_t)nchan, HW);
     return launched();
   }
   if (dt == NF_F32)
-    hipLaunchKernelGGL(avgpool_global_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)x,
+    nf_launch(avgpool_global_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)x,
                        (float*)y, (size_t)nchan, HW);
   else
-    hipLaunchKernelGGL(avgpool_global_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)x,
+    nf_launch(avgpool_global_kernel<bf16_t>, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)x,
                        (bf16_t*)y, (size_t)nchan, HW);
   return launched();
 }
@@ -567,10 +723,10 @@ nf_status netfuse_merge_transpose(const void* src, void* dst, int M, int rows, i
   const unsigned grid = grid_for(total, 256);
   hipStream_t s = (hipStream_t)stream;
   if (dt == NF_F32)
-    hipLaunchKernelGGL(merge_transpose_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)src, (float*)dst,
+    nf_launch(merge_transpose_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)src, (float*)dst,
                        M, rows, H, to_channel != 0, (size_t)total);
   else
-    hipLaunchKernelGGL(merge_transpose_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)src,
+    nf_launch(merge_transpose_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)src,
                        (bf16_t*)dst, M, rows, H, to_channel != 0, (size_t)total);
   return launched();
 }

@@ -94,6 +94,8 @@ LIN_CASES = [
     (3, 70, 256, 100, True, True, 0),        # deep load pipeline, weight rows at odd 4-byte addresses, last chunk crosses the operand end
     (2, 200, 512, 77, True, False, 2),       # the same with rows at 2-byte addresses and the 8-wave tile
     (2, 96, 256, 256, True, True, 0),        # deep pipeline, aligned
+    (64, 128, 2048, 256, True, False, 0),    # direct-to-LDS 128 x 128 tile with k-steps of 64 (long K, narrow layer)
+    (40, 256, 96, 384, False, True, 1),      # direct-to-LDS 128 x 128 tile with k-steps of 32; fewer k-steps than stages
 ]
 
 
@@ -373,6 +375,28 @@ def test_models_are_isolated_and_order_is_free(nf, dtype):
             assert torch.equal(b[i], a[p])
         for a, b in zip(clean[2:4], permd[2:4]):
             assert torch.equal(b[0, i * 64:(i + 1) * 64], a[0, p * 64:(p + 1) * 64])
+
+
+@pytest.mark.parametrize("Cin,g", [(16, 1), (16, 2), (32, 4), (32, 8), (24, 3)], ids=lambda v: str(v))
+def test_narrow_group_convs_isolate_models(nf, Cin, g):
+    """3x3 convolutions with fewer than 32 channels per group (the block-diagonal fused kernels and what
+    replaces them when a fused block would span two models): NaN / infinity in every other model's input
+    and weights leaves model m's output bit-identical and finite (Section 3: a weight set meets only its
+    own input)."""
+    M, keep, H = 3, 1, 12
+    x, w = rnd(1, M * Cin, H, H), rnd(M * Cin, Cin // g, 3, 3, std=0.1)
+    clean = nf.conv2d(dev(x, torch.bfloat16), dev(w, torch.bfloat16), M, g=g, pad=1)
+    xp, wp = x.copy(), w.copy()
+    for m in range(M):
+        if m != keep:
+            xp[0, m * Cin:(m + 1) * Cin] = np.nan
+            wp[m * Cin:(m + 1) * Cin] = np.inf
+    dirty = nf.conv2d(dev(xp, torch.bfloat16), dev(wp, torch.bfloat16), M, g=g, pad=1)
+    torch.cuda.synchronize()
+    sl = slice(keep * Cin, (keep + 1) * Cin)
+    assert torch.isfinite(dirty[0, sl].float()).all()
+    assert torch.equal(clean[0, sl], dirty[0, sl])
+    assert not torch.isfinite(dirty[0, :Cin].float()).any()
 
 
 def test_merged_equals_m_separate_launches_bitwise(nf):
