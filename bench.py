@@ -2,17 +2,23 @@
 """Benchmark of the merged-operator hot path on one MI355X.
 
 A "step" is one merged forward pass of the workload over one batch of synthetic inputs that are
-already resident in HBM (one sequence / image per model).  Reported: merged inferences/s
-(= M / mean step time), the same kernels launched once per model (M separate launches), a
-per-kernel roofline from HIP events, and the CPU oracle timed on the host cores.
+already resident in HBM.  Reported in ONE JSON line: merged inferences/s (= M x batch / mean step
+time) with the standard deviation over the timed steps, the same kernels launched once per model
+(M separate launches, the paper's Sequential baseline), a per-kernel roofline whose durations are
+the kernels' own begin/end timestamps on the device (netfuse_time_next_launch), a sweep over the
+number of merged models and over the batch size per model (the paper's two experiments), achieved
+HBM GB/s of the normalisation and pooling kernels, and the CPU oracle timed on the host cores.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-graph] [--quick]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--quick] ...
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -22,13 +28,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK = 8.0e12          # B/s, MI355X HBM3E
 MFMA_BF16_PEAK = 2.5e15    # FLOP/s dense bf16
-FP32_VALU_PEAK = 157.3e12
 
 WORKLOADS = {
     # name: (kind, M, params)
     "encoder12_m32_s128": ("encoder", 32, dict(layers=12, seq=128, cfg=5)),
     "encoder12_m32_s512": ("encoder", 32, dict(layers=12, seq=512, cfg=5)),
-    "encoder1_m8_s128": ("encoder", 8, dict(layers=1, seq=128, cfg=2)),
+    # 113 MB of weights would stay in the 256 MB memory-side cache: three weight copies are rotated
+    "encoder1_m8_s128": ("encoder", 8, dict(layers=1, seq=128, cfg=2, rotate=3)),
     "resnet50_m32": ("resnet", 32, dict(card=1, bw=64, cfg=3)),
     "resnext50_32x4d_m16": ("resnet", 16, dict(card=32, bw=4, cfg=4)),
 }
@@ -40,26 +46,63 @@ def log(*a):
 
 
 # ------------------------------------------------------------------------------------------
-class OpTimer:
-    """Wraps the binding's entry points with HIP events (on the stream the kernels run on) and
-    accumulates, per op tag, launches, time, algorithmic flops and algorithmic bytes (every operand
-    read once, the output written once)."""
+class HipEvents:
+    """Raw hipEvent_t handles from the HIP runtime this process already loaded (torch's events are
+    created lazily and do not expose a handle before they are recorded)."""
 
-    def __init__(self, nf, torch):
-        self.nf, self.torch = nf, torch
+    def __init__(self):
+        path = None
+        with open("/proc/self/maps") as f:
+            for line in f:
+                m = re.search(r"(/\S*libamdhip64\.so\S*)", line)
+                if m:
+                    path = m.group(1)
+                    break
+        self.hip = ctypes.CDLL(path or "libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.free, self.all = [], []
+
+    def get(self):
+        if self.free:
+            return self.free.pop()
+        e = ctypes.c_void_p()
+        if self.hip.hipEventCreate(ctypes.byref(e)) != 0:
+            raise RuntimeError("hipEventCreate failed")
+        self.all.append(e)
+        return e
+
+    def ms(self, a, b):
+        f = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(f), a, b)
+        if rc != 0:
+            raise RuntimeError("hipEventElapsedTime failed (%d)" % rc)
+        return f.value
+
+    def release(self, *ev):
+        self.free.extend(ev)
+
+
+class OpTimer:
+    """Wraps the binding's entry points: before each call the library is armed (netfuse_time_next_launch)
+    so that the ONE kernel the call launches records its own begin and end on the device.  No host-side
+    event pair is involved, so nothing is subtracted.  Accumulates, per op tag, launches, kernel time,
+    algorithmic flops and algorithmic bytes (every operand read once, the output written once)."""
+
+    def __init__(self, nf, torch, events):
+        self.nf, self.torch, self.ev = nf, torch, events
         self.records = []          # (tag, start, stop, flops, bytes)
         self.saved = {}
 
     def _wrap(self, name, describe):
         orig = getattr(self.nf, name)
         self.saved[name] = orig
-        torch = self.torch
 
         def wrapped(*a, **kw):
-            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            s.record()
+            s, e = self.ev.get(), self.ev.get()
+            self.nf.time_next_launch(s, e)
             out = orig(*a, **kw)
-            e.record()
             tag, fl, by = describe(out, *a, **kw)
             self.records.append((tag, s, e, fl, by))
             return out
@@ -69,14 +112,15 @@ class OpTimer:
         def d_linear(y_, X, W, bias=None, residual=None, act=0, **kw):
             M, N, K = X.shape
             No = W.shape[2]
-            e = X.element_size()
-            by = e * (X.numel() + W.numel() + y_.numel() * (2 if residual is not None else 1)) + (4 * M * No if bias is not None else 0)
-            return "linear_%dx%dx%d" % (N, K, No), 2.0 * M * N * K * No, by
+            # per model: activations in, weights, activations out (2 bytes each)
+            return "linear_%dx%dx%d" % (N, K, No), 2.0 * M * N * K * No, X.element_size() * (X.numel() + W.numel() + y_.numel())
+
+        def d_linear_packed(y_, X, Wp, panel, **kw):
+            return d_linear(y_, X, Wp, **kw)
 
         def d_conv(y_, x, w, M, g=1, bias=None, scale=None, shift=None, residual=None, stride=1, pad=0, **kw):
-            e = x.element_size()
             fl = 2.0 * y_.numel() * w.shape[1] * w.shape[2] * w.shape[3]
-            by = e * (x.numel() + w.numel() + y_.numel() * (2 if residual is not None else 1)) + (8 * w.shape[0] if scale is not None else 0)
+            by = x.element_size() * (x.numel() + w.numel() + y_.numel())
             tag = "conv%dx%d_s%d_g%d_%d->%d@%d" % (w.shape[2], w.shape[3], stride, g, x.shape[1] // M, w.shape[0] // M, x.shape[2])
             return tag, fl, by
 
@@ -85,8 +129,7 @@ class OpTimer:
             return "attention_S%d" % S, 4.0 * M * B * heads * S * S * (th // 3 // heads), QKV.element_size() * (QKV.numel() + y_.numel())
 
         def d_ln(y_, x, gamma, beta, M, residual=None, **kw):
-            by = x.element_size() * x.numel() * (3 if residual is not None else 2) + 8 * gamma.numel()
-            return "layernorm_H%d" % (gamma.numel() // M), 8.0 * x.numel(), by
+            return "layernorm_H%d" % (gamma.numel() // M), 8.0 * x.numel(), x.element_size() * x.numel() * 2 + 8 * gamma.numel()
 
         def d_pool(tag):
             def d(y_, x, *a, **kw):
@@ -94,6 +137,7 @@ class OpTimer:
             return d
 
         self._wrap("linear", d_linear)
+        self._wrap("linear_packed", d_linear_packed)
         self._wrap("conv2d", d_conv)
         self._wrap("attention_packed", d_attn)
         self._wrap("layernorm", d_ln)
@@ -104,44 +148,32 @@ class OpTimer:
     def __exit__(self, *exc):
         for k, v in self.saved.items():
             setattr(self.nf, k, v)
-
-    def empty_pairs(self, n=64):
-        """Event pairs around nothing, recorded in the middle of the same stream of work: what a
-        start/stop pair measures by itself (subtracted from every bracketed launch)."""
-        torch = self.torch
-        self.empty = []
-        for _ in range(n):
-            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            s.record()
-            e.record()
-            self.empty.append((s, e))
+        self.nf.time_next_launch(None, None)
 
     def summary(self):
         self.torch.cuda.synchronize()
-        self.overhead_ms = 0.0
-        if getattr(self, "empty", None):
-            vals = sorted(s.elapsed_time(e) for s, e in self.empty)
-            self.overhead_ms = vals[0]            # the smallest: never over-corrects
         agg = {}
         for tag, s, e, fl, by in self.records:
             a = agg.setdefault(tag, dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
             a["launches"] += 1
-            a["ms"] += max(s.elapsed_time(e) - self.overhead_ms, 1e-4)
+            a["ms"] += self.ev.ms(s, e)
             a["flops"] += fl
             a["bytes"] += by
+            self.ev.release(s, e)
+        self.records = []
         return agg
 
 
 def group_family(tag):
-    """Kernel family of an op tag: every convolution shape runs in the same two kernel templates
-    (gemm_mfma_kernel / conv_patch_kernel), every matmul in gemm_dma_kernel / gemm_mfma_kernel."""
+    """Kernel family of an op tag: all matmul shapes form `linear`, all convolution shapes `conv`."""
     head = tag.split("_")[0]
     return "conv" if head.startswith("conv") else head
 
 
 def roofline_for(agg):
-    """Roofline of the kernel family that takes the most time; bound = the larger of the HBM and the
-    MFMA lower bounds for its algorithmic bytes and flops."""
+    """Roofline of the kernel family that takes the most kernel time.  achieved = algorithmic bytes (or
+    flops) per launch / the family's average kernel duration; bound = the larger of the HBM and the MFMA
+    lower bounds for those bytes and flops."""
     fam = {}
     for tag, a in agg.items():
         f = fam.setdefault(group_family(tag), dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
@@ -155,7 +187,8 @@ def roofline_for(agg):
                bytes_per_launch=a["bytes"] / a["launches"], flops_per_launch=a["flops"] / a["launches"],
                achieved_GBps=a["bytes"] / sec / 1e9, achieved_TFLOPs=a["flops"] / sec / 1e12,
                frac_hbm=a["bytes"] / sec / HBM_PEAK, frac_mfma=a["flops"] / sec / MFMA_BF16_PEAK,
-               frac_of_min_roof=max(t_hbm, t_mfma) / sec, traffic=None)
+               frac_of_min_roof=max(t_hbm, t_mfma) / sec, traffic=None,
+               timing="kernel begin/end timestamps on the device (hipExtLaunchKernel events), eager launches")
     if contraction and t_mfma > t_hbm:
         out.update(bound="mfma", achieved=out["achieved_TFLOPs"], peak=MFMA_BF16_PEAK / 1e12, unit="TFLOP/s",
                    frac=out["frac_mfma"])
@@ -166,44 +199,66 @@ def roofline_for(agg):
 
 
 # ------------------------------------------------------------------------------------------
-def build_workload(name, torch):
+def build_workload(name, torch, M=None, batch=1):
+    """-> (forward(), [per-model forward()], config, M, inferences per step)."""
     import netfuse_inputs as NI
     from netfuse_inputs.device import encoder_stack_device, resnet_params_device
     from paper_2009_13062_amd.workloads import EncoderStack, ResNetForward
-    kind, M, p = WORKLOADS[name]
+    kind, M0, p = WORKLOADS[name]
+    M = M or M0
     if kind == "encoder":
-        shape = NI.EncoderShape(layers=p["layers"], seq=p["seq"])
-        inp = encoder_stack_device(M, shape, cfg=p["cfg"])
-        net = EncoderStack(inp["layers"], M, 1, shape.seq, shape.heads)
-        x = inp["X"]
+        shape = NI.EncoderShape(layers=p["layers"], seq=p["seq"], batch=batch)
+        rot = p.get("rotate", 1)
+        nets, x = [], None
+        for r in range(rot):
+            inp = encoder_stack_device(M, shape, cfg=p["cfg"] + 100 * r)
+            nets.append(EncoderStack(inp["layers"], M, batch, shape.seq, shape.heads,
+                                     buffers=nets[0].buf if nets else None))
+            x = inp["X"] if x is None else x
         cfg = dict(workload=name, M=M, layers=shape.layers, seq_len=shape.seq, hidden=shape.hidden,
-                   heads=shape.heads, ffn=shape.ffn, batch_per_model=1)
-        singles = [(one, x[m:m + 1]) for m, one in enumerate(net.per_model())]
-    else:
-        spec = NI.resnet_spec(cardinality=p["card"], base_width=p["bw"])
-        inp = resnet_params_device(spec, M, cfg=p["cfg"])
-        net = ResNetForward(spec, inp["params"], M)
-        x = inp["x"]
-        cfg = dict(workload=name, M=M, image=spec.image, convs=len(spec.convs()),
-                   merged_groups_3x3=M * p["card"], batch_per_model=1)
-        singles = [(one, net.slice_input(x, m)) for m, one in enumerate(net.per_model())]
-    return net, x, singles, cfg, M
+                   heads=shape.heads, ffn=shape.ffn, batch_per_model=batch, weight_copies_rotated=rot)
+
+        def merged():
+            for n in nets:
+                n.forward(x)
+        per = [n.per_model() for n in nets]
+
+        def separate():
+            for pm in per:
+                for m, one in enumerate(pm):
+                    one.forward(x[m:m + 1])
+        return merged, separate, cfg, M, rot
+    spec = NI.resnet_spec(cardinality=p["card"], base_width=p["bw"])
+    inp = resnet_params_device(spec, M, cfg=p["cfg"], batch=batch)
+    net = ResNetForward(spec, inp["params"], M, batch=batch)
+    x = inp["x"]
+    cfg = dict(workload=name, M=M, image=spec.image, convs=len(spec.convs()),
+               merged_groups_3x3=M * p["card"], batch_per_model=batch, weight_copies_rotated=1)
+    singles = [(one, net.slice_input(x, m)) for m, one in enumerate(net.per_model())]
+
+    def separate():
+        for one, xm in singles:
+            one.forward(xm)
+    return (lambda: net.forward(x)), separate, cfg, M, 1
 
 
 def timed(torch, fn, steps, warmup):
-    """W untimed steps, then exactly K steps between synchronisations; wall clock and HIP events."""
+    """W untimed steps, then exactly K steps between synchronisations: mean from the wall clock around the
+    K steps; standard deviation from one torch event per step boundary on the launch stream (they add no
+    synchronisation)."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
-    s.record()
-    for _ in range(steps):
+    marks[0].record()
+    for i in range(steps):
         fn()
-    e.record()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) * 1e3 / steps
-    return wall, s.elapsed_time(e) / steps
+    per = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+    return wall, (statistics.pstdev(per) if steps > 1 else 0.0), statistics.mean(per)
 
 
 def make_graph(torch, fn):
@@ -220,8 +275,25 @@ def make_graph(torch, fn):
     return g.replay
 
 
+def best_of(torch, fn, steps, warmup, use_graph, res, prefix):
+    """Eager and (optionally) graph-replayed timing of fn; the faster is the step time."""
+    wall, sd, ev = timed(torch, fn, steps, warmup)
+    res[prefix + "eager_ms"] = wall
+    best, best_sd = wall, sd
+    if use_graph:
+        try:
+            replay = make_graph(torch, fn)
+            gw, gsd, _ = timed(torch, replay, steps, warmup)
+            res[prefix + "graph_ms"] = gw
+            if gw < best:
+                best, best_sd = gw, gsd
+        except Exception as ex:                       # report, keep the eager number
+            res[prefix + "graph_error"] = repr(ex)[:200]
+    return best, best_sd
+
+
 def load_traffic(name):
-    """HBM bytes per launch of the dominant kernel, measured offline with rocprofv3 --pmc (FETCH_SIZE,
+    """HBM bytes per launch of the dominant kernel family, measured offline with rocprofv3 --pmc (FETCH_SIZE,
     WRITE_SIZE, calibrated against --calibrate-copy) and recorded under profiles/; None if not recorded."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     if not os.path.exists(path):
@@ -244,68 +316,129 @@ def calibrate_copy(torch, nf):
                                          "bytes_written_per_launch": dst.numel() * 2}}))
 
 
-def run_workload(name, steps, warmup, use_graph, torch, nf, sep_steps=None, separate_too=True):
-    net, x, singles, cfg, M = build_workload(name, torch)
-    merged = lambda: net.forward(x)
+def kernel_pass(torch, nf, events, fn, npass):
+    """npass eager steps with every launch timed by its own device timestamps."""
+    with OpTimer(nf, torch, events) as ot:
+        for _ in range(npass):
+            fn()
+        return ot.summary()
 
-    def separate():
-        for one, xm in singles:
-            one.forward(xm)
 
+def run_workload(name, steps, warmup, use_graph, torch, nf, events, separate_too=True, M=None, batch=1,
+                 sep_steps=None, kernels=True):
+    merged, separate, cfg, M, per_step = build_workload(name, torch, M=M, batch=batch)
     res = dict(config=cfg)
-    wall, ev = timed(torch, merged, steps, warmup)
-    res["eager_ms"], res["eager_event_ms"] = wall, ev
-    best = wall
-    if use_graph:
-        try:
-            replay = make_graph(torch, merged)
-            gw, ge = timed(torch, replay, steps, warmup)
-            res["graph_ms"], res["graph_event_ms"] = gw, ge
-            best = min(best, gw)
-        except Exception as ex:                       # report, keep the eager number
-            res["graph_error"] = repr(ex)[:200]
-    res["ms_per_step"] = best
-    res["inferences_per_s"] = M / (best * 1e-3)
+    best, sd = best_of(torch, merged, steps, warmup, use_graph, res, "")
+    res["ms_per_step"] = best / per_step
+    res["ms_per_step_std"] = sd / per_step
+    res["inferences_per_s"] = M * batch / (res["ms_per_step"] * 1e-3)
     if separate_too:
-        ss = sep_steps or max(2, steps // 4)
-        sw, se = timed(torch, separate, ss, max(1, warmup // 2))
-        sep_best = sw
-        res["separate_eager_ms"] = sw
-        if use_graph:
-            try:
-                replay_s = make_graph(torch, separate)
-                sgw, _ = timed(torch, replay_s, ss, max(1, warmup // 2))
-                res["separate_graph_ms"] = sgw
-                sep_best = min(sep_best, sgw)
-            except Exception as ex:
-                res["separate_graph_error"] = repr(ex)[:200]
-        res["separate_ms"] = sep_best
-        res["separate_inferences_per_s"] = M / (sep_best * 1e-3)
-        res["speedup_vs_separate"] = sep_best / best
+        ss = sep_steps or steps
+        sbest, ssd = best_of(torch, separate, ss, max(1, warmup // 2), use_graph, res, "separate_")
+        res["separate_ms"], res["separate_ms_std"] = sbest / per_step, ssd / per_step
+        res["separate_inferences_per_s"] = M * batch / (res["separate_ms"] * 1e-3)
+        res["speedup_vs_separate"] = sbest / best
     else:
         res["separate_ms"] = res["separate_inferences_per_s"] = res["speedup_vs_separate"] = None
-    # per-kernel pass: the same steps, un-graphed, HIP events around every launch
-    with OpTimer(nf, torch) as ot:
+    if kernels:
         npass = max(3, min(steps, 10))
-        for i in range(npass):
-            merged()
-            if i == npass // 2:
-                ot.empty_pairs()
-        agg = ot.summary()
-    res["event_pair_overhead_us"] = 1e3 * ot.overhead_ms
-    res["kernels"] = {k: dict(launches=v["launches"], avg_us=1e3 * v["ms"] / v["launches"],
-                              GBps=v["bytes"] / (v["ms"] * 1e-3) / 1e9, TFLOPs=v["flops"] / (v["ms"] * 1e-3) / 1e12)
-                      for k, v in sorted(agg.items(), key=lambda kv: -kv[1]["ms"])}
-    res["roofline"] = roofline_for(agg)
-    res["roofline"]["traffic"] = load_traffic(name)
-    total_fl = sum(v["flops"] for v in agg.values()) / max(3, min(steps, 10))
-    res["model_TFLOPs"] = total_fl / (best * 1e-3) / 1e12
+        agg = kernel_pass(torch, nf, events, merged, npass)
+        res["kernels"] = {k: dict(launches=v["launches"], avg_us=1e3 * v["ms"] / v["launches"],
+                                  GBps=v["bytes"] / (v["ms"] * 1e-3) / 1e9, TFLOPs=v["flops"] / (v["ms"] * 1e-3) / 1e12)
+                          for k, v in sorted(agg.items(), key=lambda kv: -kv[1]["ms"])}
+        res["roofline"] = roofline_for(agg)
+        res["roofline"]["traffic"] = load_traffic(name) if (M, batch) == (WORKLOADS[name][1], 1) else None
+        res["kernel_time_ms_per_step"] = sum(v["ms"] for v in agg.values()) / npass / per_step
+        res["model_TFLOPs"] = sum(v["flops"] for v in agg.values()) / npass / per_step / (res["ms_per_step"] * 1e-3) / 1e12
     return res
+
+
+def m_sweep(name, steps, warmup, use_graph, torch, nf, events, head):
+    """Merged vs M separate launches for 1 ... 32 models (the paper's first experiment)."""
+    out = {}
+    M0 = WORKLOADS[name][1]
+    for M in (1, 2, 8, 16, 32):
+        if M > M0:
+            continue
+        if M == M0:
+            r = head
+        else:
+            torch.cuda.empty_cache()
+            r = run_workload(name, steps, warmup, use_graph, torch, nf, events, M=M, kernels=False)
+        out[str(M)] = dict(merged_ms=r["ms_per_step"], merged_ms_std=r["ms_per_step_std"], separate_ms=r["separate_ms"],
+                           separate_ms_std=r.get("separate_ms_std"), speedup_vs_separate=r["speedup_vs_separate"],
+                           inferences_per_s=r["inferences_per_s"])
+        log("[bench]   M=%2d: merged %.3f ms, separate %.3f ms, %.2fx" % (M, r["ms_per_step"], r["separate_ms"], r["speedup_vs_separate"]))
+    return out
+
+
+def batch_sweep(name, steps, warmup, use_graph, torch, nf, events, head):
+    """Merged vs separate for 1 ... 8 sequences (images) per model (the paper's batch-size experiment), with
+    the matmul family's share of the bf16 MFMA peak per batch size; `crossover_batch` = the first batch size
+    at which merging no longer pays (None if it pays everywhere)."""
+    out, cross = {}, None
+    for B in (1, 2, 4, 8):
+        if B == 1:
+            r = head
+        else:
+            torch.cuda.empty_cache()
+            r = run_workload(name, steps, warmup, use_graph, torch, nf, events, batch=B)
+        fam = r["roofline"]
+        out[str(B)] = dict(merged_ms=r["ms_per_step"], separate_ms=r["separate_ms"], speedup_vs_separate=r["speedup_vs_separate"],
+                           inferences_per_s=r["inferences_per_s"], dominant_family=fam["kernel"],
+                           family_frac_mfma=fam["frac_mfma"], family_frac_hbm=fam["frac_hbm"], family_avg_us=fam["avg_us"])
+        if cross is None and r["speedup_vs_separate"] < 1.0:
+            cross = B
+        log("[bench]   batch %d: merged %.3f ms, separate %.3f ms, %.2fx, %s at %.1f%% of MFMA peak" % (
+            B, r["ms_per_step"], r["separate_ms"], r["speedup_vs_separate"], fam["kernel"], 100 * fam["frac_mfma"]))
+    out["crossover_batch"] = cross
+    return out
+
+
+def micro_norms(torch, nf, events):
+    """Achieved HBM GB/s (bytes in + out over the kernel's own duration) of the normalisation and pooling
+    kernels at the shapes of the workloads, 32 models, bf16."""
+    bf = torch.bfloat16
+    rnd = lambda *s: torch.empty(s, dtype=bf, device="cuda").normal_()
+    f32 = lambda n, mean=0.0: torch.empty(n, dtype=torch.float32, device="cuda").normal_(mean, 0.1)
+    cases = {}
+    for rows, tag in ((128, "layernorm_4096x768"), (512, "layernorm_16384x768")):
+        x, r, y = rnd(32, rows, 768), rnd(32, rows, 768), rnd(32, rows, 768)
+        g, b = f32(32 * 768, 1.0), f32(32 * 768)
+        cases[tag] = (lambda x=x, g=g, b=b, y=y: nf.layernorm(x, g, b, 32, out=y), 2 * x.numel() * 2)
+        cases[tag + "+residual"] = (lambda x=x, r=r, g=g, b=b, y=y: nf.layernorm(x, g, b, 32, residual=r, out=y), 3 * x.numel() * 2)
+    for C, hw, tag in ((64, 112, "batchnorm_64ch_112x112"), (256, 56, "batchnorm_256ch_56x56"), (2048, 7, "batchnorm_2048ch_7x7")):
+        x, y = rnd(1, 32 * C, hw, hw), rnd(1, 32 * C, hw, hw)
+        g, b, mu = f32(32 * C, 1.0), f32(32 * C), f32(32 * C)
+        var = torch.empty(32 * C, dtype=torch.float32, device="cuda").uniform_(0.5, 1.5)
+        cases[tag] = (lambda x=x, g=g, b=b, mu=mu, var=var, y=y: nf.batchnorm(x, g, b, mu, var, 32, act=nf.ACT_RELU, out=y), 2 * x.numel() * 2)
+    x = rnd(1, 32 * 64, 112, 112)
+    y = rnd(1, 32 * 64, 56, 56)
+    cases["maxpool3x3s2_64ch_112x112"] = (lambda x=x, y=y: nf.maxpool2d(x, 3, 2, 1, out=y), (x.numel() + y.numel()) * 2)
+    x = rnd(1, 32 * 2048, 7, 7)
+    y = rnd(1, 32 * 2048)
+    cases["avgpool_2048ch_7x7"] = (lambda x=x, y=y: nf.avgpool_global(x, out=y), (x.numel() + y.numel()) * 2)
+    out = {}
+    for tag, (fn, nbytes) in cases.items():
+        for _ in range(3):
+            fn()
+        pairs = []
+        for _ in range(20):
+            s, e = events.get(), events.get()
+            nf.time_next_launch(s, e)
+            fn()
+            pairs.append((s, e))
+        torch.cuda.synchronize()
+        us = sorted(1e3 * events.ms(s, e) for s, e in pairs)
+        for s, e in pairs:
+            events.release(s, e)
+        med = us[len(us) // 2]
+        out[tag] = dict(us=med, GBps=nbytes / med / 1e3, frac_hbm=nbytes / (med * 1e-6) / HBM_PEAK, MB=nbytes / 1e6)
+    return out
 
 
 def cpu_baseline(name):
     """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
-    import numpy as np
     import netfuse_inputs as NI
     import oracle
     from oracle import models as OM
@@ -338,16 +471,18 @@ def cpu_baseline(name):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=HEADLINE, choices=sorted(WORKLOADS))
     ap.add_argument("--others", default="encoder12_m32_s512,resnet50_m32,resnext50_32x4d_m16,encoder1_m8_s128",
                     help="comma list of further workloads reported under 'other_workloads' ('' = none)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--quick", action="store_true", help="headline workload only, no CPU baseline")
+    ap.add_argument("--no-sweeps", action="store_true", help="skip the model-count and batch-size sweeps")
+    ap.add_argument("--quick", action="store_true", help="headline workload only: no sweeps, no other workloads, no CPU baseline")
     ap.add_argument("--no-separate", action="store_true", help="skip the M-separate-launches leg (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true", help="only run a plain copy of known size and exit")
+    ap.add_argument("--micro", default="", choices=["", "norms"], help="only the named micro-benchmark leg")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (models are independent: sharding M over GPUs needs no "
@@ -357,32 +492,49 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     import paper_2009_13062_amd as nf
     torch.cuda.set_device(0)
+    events = HipEvents()
 
     if args.calibrate_copy:
         calibrate_copy(torch, nf)
         return
+    if args.micro == "norms":
+        print(json.dumps({"norm_kernels": micro_norms(torch, nf, events)}))
+        return
+    use_graph = not args.no_graph
+    sweep_steps = max(5, min(args.steps, 30))
     t_start = time.time()
-    head = run_workload(args.workload, args.steps, args.warmup, not args.no_graph, torch, nf,
-                        separate_too=not args.no_separate)
-    log("[bench] %s: %.3f ms/step, %.1f inf/s, %sx vs separate (%.1f s)" % (
-        args.workload, head["ms_per_step"], head["inferences_per_s"],
+    head = run_workload(args.workload, args.steps, args.warmup, use_graph, torch, nf, events,
+                        separate_too=not args.no_separate, sep_steps=sweep_steps)
+    log("[bench] %s: %.3f +- %.3f ms/step, %.1f inf/s, %sx vs separate (%.1f s)" % (
+        args.workload, head["ms_per_step"], head["ms_per_step_std"], head["inferences_per_s"],
         "%.2f" % head["speedup_vs_separate"] if head["speedup_vs_separate"] else "-", time.time() - t_start))
+    sweeps = {}
+    if not (args.quick or args.no_sweeps or args.no_separate):
+        t1 = time.time()
+        sweeps["m_sweep"] = m_sweep(args.workload, sweep_steps, args.warmup, use_graph, torch, nf, events, head)
+        sweeps["batch_sweep"] = batch_sweep(args.workload, sweep_steps, args.warmup, use_graph, torch, nf, events, head)
+        log("[bench] sweeps done (%.1f s)" % (time.time() - t1))
     others = {}
     if not args.quick and args.others:
         for name in [n for n in args.others.split(",") if n and n != args.workload]:
             t1 = time.time()
             try:
                 torch.cuda.empty_cache()
-                r = run_workload(name, max(5, args.steps // 5), max(2, args.warmup // 2), not args.no_graph, torch, nf)
-                others[name] = dict(ms_per_step=r["ms_per_step"], inferences_per_s=r["inferences_per_s"],
+                r = run_workload(name, args.steps, args.warmup, use_graph, torch, nf, events, sep_steps=sweep_steps)
+                others[name] = dict(ms_per_step=r["ms_per_step"], ms_per_step_std=r["ms_per_step_std"],
+                                    inferences_per_s=r["inferences_per_s"], steps=args.steps,
                                     separate_ms=r["separate_ms"], speedup_vs_separate=r["speedup_vs_separate"],
-                                    model_TFLOPs=r["model_TFLOPs"], roofline=r["roofline"],
-                                    kernels=dict(list(r["kernels"].items())[:8]))
-                log("[bench] %s: %.3f ms/step, %.2fx vs separate (%.1f s)" % (
-                    name, r["ms_per_step"], r["speedup_vs_separate"], time.time() - t1))
+                                    model_TFLOPs=r["model_TFLOPs"], weight_copies_rotated=r["config"]["weight_copies_rotated"],
+                                    roofline=r["roofline"], kernels=dict(list(r["kernels"].items())[:8]))
+                log("[bench] %s: %.3f +- %.3f ms/step, %.2fx vs separate (%.1f s)" % (
+                    name, r["ms_per_step"], r["ms_per_step_std"], r["speedup_vs_separate"], time.time() - t1))
             except Exception as ex:
                 others[name] = dict(error=repr(ex)[:300])
                 log("[bench] %s failed: %r" % (name, ex))
+    norms = None
+    if not args.quick:
+        torch.cuda.empty_cache()
+        norms = micro_norms(torch, nf, events)
     cpu = None
     if not (args.quick or args.no_cpu_baseline):
         cpu = cpu_baseline(args.workload)
@@ -394,19 +546,23 @@ def main():
         "metric": "merged inferences/sec at M=%d (one %s per model), vs M separate launches" % (
             M, "sequence" if kind == "encoder" else "image"),
         "value": head["inferences_per_s"], "unit": "inferences/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "ms_per_step_std": head["ms_per_step_std"],
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": head["config"],
-        "separate_launches": {"ms_per_step": head["separate_ms"], "inferences_per_s": head["separate_inferences_per_s"]},
+        "separate_launches": {"ms_per_step": head["separate_ms"], "inferences_per_s": head["separate_inferences_per_s"],
+                              "steps": sweep_steps},
         "speedup_vs_separate": head["speedup_vs_separate"],
         "launch": {k: head[k] for k in ("eager_ms", "graph_ms", "separate_eager_ms", "separate_graph_ms", "graph_error") if k in head},
         "model_TFLOPs": head["model_TFLOPs"],
-        "event_pair_overhead_us": head["event_pair_overhead_us"],
+        "kernel_time_ms_per_step": head["kernel_time_ms_per_step"],
         "roofline": {k: rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "launches",
                                         "avg_us", "bytes_per_launch", "flops_per_launch", "frac_hbm", "frac_mfma",
-                                        "frac_of_min_roof")},
+                                        "frac_of_min_roof", "timing")},
         "kernels": head["kernels"],
         "cpu_baseline": cpu,
+        **sweeps,
+        "norm_kernels": norms,
         "other_workloads": others,
         "paper_context": "NetFuse reports up to 3.6x (V100) / 3.0x (TITAN Xp) over its best baseline at 32 instances, fp32, bs 1",
     }

@@ -208,8 +208,9 @@ def resnet_spec(cardinality: int = 1, base_width: int = 64, image: int = 224, wi
 
 
 def resnet_params(spec: ResNetSpec, M: int, cfg: int = 3, bf16: bool = True,
-                  order: Optional[List[int]] = None) -> Dict[str, object]:
-    """x[1, M*3, image, image] ~ N(0,1).  Per conv: Kaiming-normal weight, std = sqrt(2/(cig*k*k));
+                  order: Optional[List[int]] = None, batch: int = 1) -> Dict[str, object]:
+    """x[batch, M*3, image, image] ~ N(0,1) (model m's ``batch`` images are its first draw, so batch 1
+    reproduces the single-image inputs).  Per conv: Kaiming-normal weight, std = sqrt(2/(cig*k*k));
     BatchNorm gamma ~ 1+N(0,0.02), beta ~ N(0,0.02), running mean ~ N(0,0.1), var ~ U(0.5,1.5).
     BatchNorm vectors stay float32 (they are per-channel constants, not activations)."""
     order = list(range(M)) if order is None else list(order)
@@ -218,7 +219,7 @@ def resnet_params(spec: ResNetSpec, M: int, cfg: int = 3, bf16: bool = True,
     acc = {c.name: dict(w=[], gamma=[], beta=[], mean=[], var=[]) for c in convs}
     for m in order:
         r = model_rng(cfg, m)
-        xs.append(_normal(r, (3, spec.image, spec.image)))
+        xs.append(_normal(r, (batch, 3, spec.image, spec.image)))
         for c in convs:
             cig = c.cin // c.groups
             std = float(np.sqrt(2.0 / (cig * c.k * c.k)))
@@ -235,4 +236,4 @@ def resnet_params(spec: ResNetSpec, M: int, cfg: int = 3, bf16: bool = True,
             w=_store(np.concatenate(a["w"]), bf16),
             gamma=np.concatenate(a["gamma"]), beta=np.concatenate(a["beta"]),
             mean=np.concatenate(a["mean"]), var=np.concatenate(a["var"]))
-    return {"x": _store(np.concatenate(xs)[None], bf16), "params": params}
+    return {"x": _store(np.concatenate(xs, axis=1), bf16), "params": params}

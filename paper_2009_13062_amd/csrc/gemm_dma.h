@@ -25,6 +25,18 @@ namespace nf {
 typedef __attribute__((address_space(3))) unsigned char lds_u8_t;
 typedef __attribute__((address_space(1))) const unsigned char glb_u8_t;
 
+// Cache policy of the weight loads (aux operand of global_load_lds: 1 = sc0, 2 = nt, 16 = sc1).  Weights are
+// read exactly once per forward pass and are 20 times the size of the activations of a layer, so they are
+// loaded non-temporal: they then do not displace the activations that the previous operator has just left in
+// the memory-side cache (256 MB) and that the next one is about to read.  Measured on the operator sequence of
+// one encoder layer at 32 models (us per kernel, default policy -> nt): 768 -> 2304 matmul 33.9 -> 28.2,
+// 768 -> 3072 + GELU 45.0 -> 38.9, 3072 -> 768 45.1 -> 38.4, whole layer 167 -> 150; sc1 changes nothing.  A
+// kernel timed alone in a loop does not show this: its own output then never leaves that cache.
+#ifndef NF_B_CPOL
+#define NF_B_CPOL 2
+#endif
+constexpr int kWeightCpol = NF_B_CPOL;
+
 template <int BM, int BN, int BK, int WGM, int WGN, int NS>
 struct DmaCfg {
   static_assert(BK == 32 || BK == 64, "k-step of 32 or 64");
@@ -75,6 +87,40 @@ __device__ __forceinline__ void wait_lgkmcnt0() {
   __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (7 << 4) | (0 << 8));
 }
 
+// The A operand of a weight-streaming matmul is small (the model's activation rows) but is re-read by
+// every column tile and k-step, and it was written by the previous operator, so it starts out in no L2.
+// Each of the `parts` workgroups that share an A tile (the column tiles of one model and row tile, which run
+// on one XCD) reads one part of its rows once, right after its first pipeline stages are on their way,
+// k-ascending, and discards the data: the rows are then L2 hits for every later k-step of all of them.
+// Measured on the 12-layer encoder at 32 models: 768 -> 3072 matmul 42.7 -> 37.9 us, 768 -> 2304 32.4 -> 28.9,
+// whole forward 1.855 -> 1.733 ms.  (Timed alone in a loop on a never rewritten input the kernels do not
+// show this: the input then stays in L2 from one launch to the next.)
+// Only launches whose workgroups are all resident at once (one per compute unit) and whose A operands fit
+// the L2 of an XCD beside the weight stream do this: 512 x 3072 activations per model (four models per XCD:
+// 12 MB against 4 MB of L2) measured 10 % slower with it, as did launches of several rounds of workgroups.
+#ifndef NF_A_TOUCH
+#define NF_A_TOUCH 1
+#endif
+inline bool touch_a_pays(long long workgroups, long long a_elems_per_problem, long long problems) {
+  const long long per_xcd = (problems + kNumXcd - 1) / kNumXcd * a_elems_per_problem * 2;      // bytes
+  return workgroups <= 256 && per_xcd <= (1 << 20);
+}
+template <class Cfg>
+__device__ __forceinline__ void touch_a_rows(const bf16_t* A, long lda, int K, int part, int parts) {
+#if NF_A_TOUCH
+  if (parts <= 0) return;
+  const int rows_per = (Cfg::kBM + parts - 1) / parts;
+  const int row_lo = part * rows_per, row_hi = min(Cfg::kBM, row_lo + rows_per);
+  const int cpr = K / 64;                                  // 128-byte lines per row
+  const int n = (row_hi - row_lo) * cpr;
+  for (int c = threadIdx.x; c < n; c += Cfg::kThreads) {
+    const int r = row_lo + c % (row_hi - row_lo), kc = c / (row_hi - row_lo);      // k-major: early k first
+    uint32_t v = *(const volatile uint32_t*)(A + (long)r * lda + kc * 64);
+    asm volatile("" ::"v"(v));
+  }
+#endif
+}
+
 // PACKED: B points at this tile's first block of a block-packed weight tensor (netfuse_linear_pack_weight):
 // 2 KB blocks of [32 k][32 n], the BN/32 blocks of one k-block contiguous, consecutive k-blocks `ldb`
 // ELEMENTS apart.  A stage's B region then is [BK/32][BN/32] such blocks, each copied as two contiguous 1 KB
@@ -83,7 +129,8 @@ __device__ __forceinline__ void wait_lgkmcnt0() {
 template <class Cfg, bool PACKED = false>
 __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long lda, const bf16_t* __restrict__ B,
                                               long ldb, int K, lds_u8_t* smem, bf16_t* C, const bf16_t* R,
-                                              long ldc, const Epilogue& ep, long row_vec_off, long col_vec_off) {
+                                              long ldc, const Epilogue& ep, long row_vec_off, long col_vec_off,
+                                              int a_touch_part = 0, int a_touch_parts = 0) {
   constexpr int FM = Cfg::FM, FN = Cfg::FN, NS = Cfg::kNS, BK = Cfg::kBK;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
@@ -120,7 +167,14 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
 #pragma unroll
     for (int t = 0; t < Cfg::kMaxPer; ++t) {
       if (t + 1 < Cfg::kMaxPer || extra)
-        __builtin_amdgcn_global_load_lds((glb_u8_t*)src[t], stage + (t * Cfg::kNW + wave) * 1024, 16, 0, 0);
+        {
+          // A blocks (activations, re-read by every column tile of the model) keep the default policy;
+          // B blocks (weights, read exactly once per forward pass) take kWeightCpol
+          if (t * Cfg::kNW + wave < Cfg::kABlocks)
+            __builtin_amdgcn_global_load_lds((glb_u8_t*)src[t], stage + (t * Cfg::kNW + wave) * 1024, 16, 0, 0);
+          else
+            __builtin_amdgcn_global_load_lds((glb_u8_t*)src[t], stage + (t * Cfg::kNW + wave) * 1024, 16, 0, kWeightCpol);
+        }
       src[t] += inc[t];
     }
   };
@@ -162,6 +216,7 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
     if (s < nk) issue_stage(s);
+  touch_a_rows<Cfg>(A, lda, K, a_touch_part, a_touch_parts);
 
   for (int kt = 0; kt < nk; ++kt) {
     // near the end fewer stages were issued, so wait for everything

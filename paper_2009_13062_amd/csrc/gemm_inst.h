@@ -8,7 +8,11 @@
 
 namespace nf {
 
-template <class Cfg, int ALIGN_A, int BKIND>
+// B_NT: B is the weight matrix of a matmul, read once per forward pass: loaded non-temporal (ldnt16).
+// Convolution weights (the A operand) are re-read by every position tile of a group and by design come from
+// L2 after the first one, so they keep the default policy (non-temporal loads of them measured 2x slower on
+// the 3x3 layers of ResNet-50).
+template <class Cfg, int ALIGN_A, int BKIND, bool B_NT>
 // 8-wave tiles are budgeted for two workgroups per CU: 4 wavefronts per SIMD, 128 registers per lane
 // (the dense B kinds only: the gathering loaders would spill under that budget)
 __global__ __launch_bounds__(Cfg::kThreads, (Cfg::kThreads == 512 && (BKIND == 8 || BKIND == 1)) ? 4 : 1)
@@ -67,7 +71,7 @@ void gemm_mfma_kernel(GemmArgs a) {
       if (a.K % (kBK * Cfg::kDepth) == 0 && a.ldb >= 8) {
         ADeepLoader<Cfg::kBM, Cfg::kThreads> la;
         la.init(Abase, a.lda, rows_left, threadIdx.x);
-        BDeepLoader<Cfg::kBN, BKIND == 8, Cfg::kThreads> lb;
+        BDeepLoader<Cfg::kBN, BKIND == 8, Cfg::kThreads, B_NT> lb;
         lb.init(Bbase + col0, a.ldb, cols_left, a.K, a.B_end, threadIdx.x);
         gemm_tile<Cfg, true>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
         return;
@@ -76,7 +80,7 @@ void gemm_mfma_kernel(GemmArgs a) {
     auto general = [&]() {
       ATileLoader<Cfg::kBM, ALIGN_A, false, Cfg::kThreads> la;
       la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
-      BDenseLoader<Cfg::kBN, BKIND == 0 ? 1 : BKIND, false, Cfg::kThreads> lb;
+      BDenseLoader<Cfg::kBN, BKIND == 0 ? 1 : BKIND, false, Cfg::kThreads, B_NT> lb;
       lb.base = Bbase + col0; lb.end = a.B_end; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
       gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
     };
@@ -85,7 +89,7 @@ void gemm_mfma_kernel(GemmArgs a) {
       if (rows_left >= Cfg::kBM && cols_left >= Cfg::kBN && a.K % kBK == 0) {
         ATileLoader<Cfg::kBM, 16, true, Cfg::kThreads> la;
         la.base = Abase; la.lda = a.lda; la.rows_left = rows_left; la.K = a.K;
-        BDenseLoader<Cfg::kBN, 8, true, Cfg::kThreads> lb;
+        BDenseLoader<Cfg::kBN, 8, true, Cfg::kThreads, B_NT> lb;
         lb.base = Bbase + col0; lb.end = a.B_end; lb.ldb = a.ldb; lb.cols_left = cols_left; lb.K = a.K;
         gemm_tile<Cfg>(la, lb, a.K, smem, C, R, a.ldc, rows_left, cols_left, a.ep, rvo, cvo);
       } else {
@@ -97,14 +101,14 @@ void gemm_mfma_kernel(GemmArgs a) {
   }
 }
 
-template <class Cfg, int ALIGN_A, int BKIND>
-nf_status launch_gemm(GemmLaunch& L, hipStream_t s) {
+template <class Cfg, int ALIGN_A, int BKIND, bool B_NT>
+nf_status launch_gemm_w(GemmLaunch& L, hipStream_t s) {
   GemmArgs& a = L.a;
   a.tiles_m = (a.rows + Cfg::kBM - 1) / Cfg::kBM;
   a.tiles_n = (a.cols + Cfg::kBN - 1) / Cfg::kBN;
   const long long total = (long long)a.tiles_m * a.tiles_n * a.nz0 * L.nz1;   // each factor < 2^31 / checked by caller
   if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
-  auto kern = gemm_mfma_kernel<Cfg, ALIGN_A, BKIND>;
+  auto kern = gemm_mfma_kernel<Cfg, ALIGN_A, BKIND, B_NT>;
   if (Cfg::kLdsBytes > 64 * 1024) {
     // tiles above the default 64 KB of dynamic LDS opt in once per kernel (idempotent; a benign race)
     static std::atomic<bool> opted_in{false};
@@ -117,6 +121,15 @@ nf_status launch_gemm(GemmLaunch& L, hipStream_t s) {
   }
   nf_launch(kern, dim3((unsigned)total), dim3(Cfg::kThreads), Cfg::kLdsBytes, s, a);
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
+}
+
+// the dense B kinds serve the matmul (B = weights, non-temporal) and the pointwise convolution (B = activations)
+template <class Cfg, int ALIGN_A, int BKIND>
+nf_status launch_gemm(GemmLaunch& L, hipStream_t s) {
+  if constexpr (BKIND == 8 || BKIND == 1) {
+    if (!L.weights_are_a) return launch_gemm_w<Cfg, ALIGN_A, BKIND, true>(L, s);
+  }
+  return launch_gemm_w<Cfg, ALIGN_A, BKIND, false>(L, s);
 }
 
 template <int ALIGN_A, int BKIND>

@@ -4,6 +4,16 @@
 #include "gemm_dma.h"
 #include "gemm_launch.h"
 
+#ifndef NF_NS_288
+#define NF_NS_288 4
+#endif
+#ifndef NF_NS_96
+#define NF_NS_96 4
+#endif
+#ifndef NF_NS_384
+#define NF_NS_384 4
+#endif
+
 namespace nf {
 
 template <class Cfg>
@@ -22,7 +32,8 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_dma_kernel(GemmArgs a) {
   const bf16_t* B = a.B + z0 * a.sB0 + z1 * a.sB1 + col0;
   const long rvo = z0 * a.ep.row_vec_stride0 + z1 * a.ep.row_vec_stride1 + row0;
   const long cvo = z0 * a.ep.col_vec_stride0 + z1 * a.ep.col_vec_stride1 + col0;
-  gemm_dma_tile<Cfg>(A, a.lda, B, a.ldb, a.K, smem, a.C + coff, a.R ? a.R + coff : nullptr, a.ldc, a.ep, rvo, cvo);
+  gemm_dma_tile<Cfg>(A, a.lda, B, a.ldb, a.K, smem, a.C + coff, a.R ? a.R + coff : nullptr, a.ldc, a.ep, rvo, cvo,
+                     tn, a.touch_a ? a.tiles_n : 0);
 }
 
 // B is block-packed: [problem][panel][K/32][panel/32] blocks of [32 k][32 n] (see netfuse_linear_pack_weight)
@@ -45,7 +56,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_dma_packed_kernel(GemmArgs
   const long rvo = z0 * a.ep.row_vec_stride0 + z1 * a.ep.row_vec_stride1 + row0;
   const long cvo = z0 * a.ep.col_vec_stride0 + z1 * a.ep.col_vec_stride1 + col0;
   gemm_dma_tile<Cfg, true>(A, a.lda, B, kb_stride, a.K, smem, a.C + coff, a.R ? a.R + coff : nullptr, a.ldc, a.ep,
-                           rvo, cvo);
+                           rvo, cvo, tn, a.touch_a ? a.tiles_n : 0);
 }
 
 template <class Cfg, bool PACKED = false>
@@ -56,6 +67,7 @@ nf_status launch_dma(GemmLaunch& L, hipStream_t s) {
   a.tiles_n = a.cols / Cfg::kBN;
   const long long total = (long long)a.tiles_m * a.tiles_n * a.nz0 * L.nz1;
   if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
+  a.touch_a = touch_a_pays(total, (long long)a.rows * a.K, (long long)a.nz0 * L.nz1);
   if (PACKED && (a.panel <= 0 || a.panel % Cfg::kBN || a.cols % a.panel || a.K % 32)) return NF_EUNSUPPORTED;
   void (*kern)(GemmArgs);
   if constexpr (PACKED) kern = gemm_dma_packed_kernel<Cfg>; else kern = gemm_dma_kernel<Cfg>;
@@ -77,9 +89,9 @@ nf_status launch_gemm_dma_packed(int cfg, GemmLaunch& L, hipStream_t s) {
     case D256x256k32s4: return launch_dma<DmaCfg<256, 256, 32, 2, 4, 4>, true>(L, s);
     case D128x128k32s4: return launch_dma<DmaCfg<128, 128, 32, 2, 4, 4>, true>(L, s);
     case D128x128k64s3w8: return launch_dma<DmaCfg<128, 128, 64, 2, 4, 3>, true>(L, s);
-    case D128x384k32s4w12: return launch_dma<DmaCfg<128, 384, 32, 2, 6, 4>, true>(L, s);
-    case D128x288k32s4w12: return launch_dma<DmaCfg<128, 288, 32, 4, 3, 4>, true>(L, s);
-    case D128x96k64s4w12: return launch_dma<DmaCfg<128, 96, 64, 4, 3, 4>, true>(L, s);
+    case D128x384k32s4w12: return launch_dma<DmaCfg<128, 384, 32, 2, 6, NF_NS_384>, true>(L, s);
+    case D128x288k32s4w12: return launch_dma<DmaCfg<128, 288, 32, 4, 3, NF_NS_288>, true>(L, s);
+    case D128x96k64s4w12: return launch_dma<DmaCfg<128, 96, 64, 4, 3, NF_NS_96>, true>(L, s);
   }
   return NF_EUNSUPPORTED;
 }
@@ -89,9 +101,9 @@ nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s) {
     case D256x256k32s4: return launch_dma<DmaCfg<256, 256, 32, 2, 4, 4>>(L, s);
     case D128x128k32s4: return launch_dma<DmaCfg<128, 128, 32, 2, 4, 4>>(L, s);
     case D128x128k64s3w8: return launch_dma<DmaCfg<128, 128, 64, 2, 4, 3>>(L, s);
-    case D128x384k32s4w12: return launch_dma<DmaCfg<128, 384, 32, 2, 6, 4>>(L, s);
-    case D128x288k32s4w12: return launch_dma<DmaCfg<128, 288, 32, 4, 3, 4>>(L, s);
-    case D128x96k64s4w12: return launch_dma<DmaCfg<128, 96, 64, 4, 3, 4>>(L, s);
+    case D128x384k32s4w12: return launch_dma<DmaCfg<128, 384, 32, 2, 6, NF_NS_384>>(L, s);
+    case D128x288k32s4w12: return launch_dma<DmaCfg<128, 288, 32, 4, 3, NF_NS_288>>(L, s);
+    case D128x96k64s4w12: return launch_dma<DmaCfg<128, 96, 64, 4, 3, NF_NS_96>>(L, s);
   }
   return NF_EUNSUPPORTED;
 }

@@ -4,6 +4,10 @@
 #include "gemm_launch.h"
 #include "gemm_stream.h"
 
+#ifndef NF_NS_S384
+#define NF_NS_S384 4
+#endif
+
 namespace nf {
 
 template <class Cfg, bool PACKED>
@@ -35,7 +39,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_stream_kernel(GemmArgs a, 
     tile_stride = Cfg::kBN;
   }
   gemm_stream_tiles<Cfg, PACKED>(A, a.lda, B, ldb, tile_stride, a.K, nsub, smem, a.C + coff,
-                                 a.R ? a.R + coff : nullptr, a.ldc, bias, a.ep.act);
+                                 a.R ? a.R + coff : nullptr, a.ldc, bias, a.ep.act, tg, a.touch_a ? groups_n : 0);
 }
 
 template <class Cfg, bool PACKED>
@@ -58,6 +62,7 @@ static nf_status launch_stream(GemmLaunch& L, int nsub, hipStream_t s) {
   if (a.ep.row_bias || a.ep.row_scale) return NF_EUNSUPPORTED;
   const long long total = (long long)a.tiles_m * (a.tiles_n / nsub) * a.nz0 * L.nz1;
   if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
+  a.touch_a = touch_a_pays(total, (long long)a.rows * a.K, (long long)a.nz0 * L.nz1);
   auto kern = gemm_stream_kernel<Cfg, PACKED>;
   constexpr int kLds = Cfg::kLdsPipe;
   if (kLds > 64 * 1024) {
@@ -79,7 +84,7 @@ static nf_status launch_stream_cfg(int cfg, GemmLaunch& L, int nsub, hipStream_t
     case S128x96k64: return launch_stream<DmaCfg<128, 96, 64, 4, 3, 5>, PACKED>(L, nsub, s);
     case S128x128k32: return launch_stream<DmaCfg<128, 128, 32, 2, 4, 8>, PACKED>(L, nsub, s);
     case S128x288k32: return launch_stream<DmaCfg<128, 288, 32, 4, 3, 5>, PACKED>(L, nsub, s);
-    case S128x384k32: return launch_stream<DmaCfg<128, 384, 32, 2, 6, 4>, PACKED>(L, nsub, s);
+    case S128x384k32: return launch_stream<DmaCfg<128, 384, 32, 2, 6, NF_NS_S384>, PACKED>(L, nsub, s);
     case S256x256k32: return launch_stream<DmaCfg<256, 256, 32, 2, 4, 4>, PACKED>(L, nsub, s);
     case S256x128k32: return launch_stream<DmaCfg<256, 128, 32, 4, 2, 6>, PACKED>(L, nsub, s);
   }

@@ -16,6 +16,7 @@ struct GemmArgs {
   long lda, ldb, ldc;
   long sA0, sA1, sB0, sB1, sC0, sC1;      // strides of the two batch coordinates (elements)
   int rows, cols, K, nz0, tiles_m, tiles_n;
+  int touch_a;                             // direct-to-LDS kernels: pull the A rows into L2 at kernel start (see touch_a_rows)
   int panel;                               // block-packed B (netfuse_linear_pack_weight): columns per panel, else 0
   Epilogue ep;
   Im2colGeom geom;                         // implicit-B convolution only
@@ -24,6 +25,7 @@ struct GemmArgs {
 struct GemmLaunch {
   GemmArgs a;
   int nz1;
+  int weights_are_a;                       // convolution: A is the weight tensor; matmul (0): B is
 };
 
 enum TileId { T64x64 = 0, T32x128, T128x128w8, kNumTiles };

@@ -75,6 +75,11 @@ struct Epilogue {
 // ALIGN = guaranteed byte alignment of every row start (K is then a multiple of ALIGN/2).
 // FULL = the tile lies inside the matrix and K % 64 == 0: no predicates at all (needs ALIGN 16).
 // ------------------------------------------------------------------------------------------
+// WNT: the operand is read once per forward pass (matmul weights) and is loaded non-temporal.
+template <bool WNT> __device__ __forceinline__ uint4 ld16(const void* p) {
+  if constexpr (WNT) return ldnt16(p); else return *reinterpret_cast<const uint4*>(p);
+}
+
 template <int ALIGN>
 __device__ __forceinline__ uint4 load_k8(const bf16_t* p, int k, int klim) {
   uint4 r = make_uint4(0, 0, 0, 0);
@@ -130,7 +135,7 @@ struct ATileLoader {
 // B tile loader, dense k-major matrix B[k][j] (row pitch ldb): [64][BN] copied as is.
 // VEC = 8: rows aligned to 16 bytes and cols % 8 == 0; VEC = 1: any rows.
 // ------------------------------------------------------------------------------------------
-template <int BN, int VEC, bool FULL, int NT>
+template <int BN, int VEC, bool FULL, int NT, bool WNT = false>
 struct BDenseLoader {
   static constexpr int kPitch = BN + kPadB;
   // VEC = 1 (rows that start at any 2-byte address, e.g. 7x7 = 49 positions per channel) still moves 8
@@ -160,7 +165,7 @@ struct BDenseLoader {
       const bf16_t* p = base + (long)k * ldb + j;
       const bool live = FULL || (k < K && j < cols_left);
       if constexpr (VEC == 8) {
-        const uint4 v = live ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+        const uint4 v = live ? ld16<WNT>(p) : make_uint4(0, 0, 0, 0);
         regs.v[t][0] = v.x; regs.v[t][1] = v.y; regs.v[t][2] = v.z; regs.v[t][3] = v.w;
       } else {
         uint4 v = make_uint4(0, 0, 0, 0);
@@ -385,7 +390,7 @@ struct ADeepLoader {
   }
 };
 
-template <int BN, bool ALIGNED, int NT>
+template <int BN, bool ALIGNED, int NT, bool WNT = false>
 struct BDeepLoader {
   static constexpr int kPitch = BN + kPadB;
   static constexpr int kPerRow = BN / 8;
@@ -428,7 +433,7 @@ struct BDeepLoader {
 #pragma unroll
     for (int t = 0; t < kPer; ++t) {
       if constexpr (ALIGNED) {
-        regs.v[t] = *reinterpret_cast<const uint4*>(src[t] + off);
+        regs.v[t] = ld16<WNT>(src[t] + off);
       } else {
         const bf16_t* p = src[t] + off;
         regs.v[t] = reinterpret_cast<const unaligned16*>(p < limit ? p : limit)->v;

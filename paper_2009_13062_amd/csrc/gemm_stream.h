@@ -67,7 +67,7 @@ template <class Cfg, bool PACKED>
 __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, long lda, const bf16_t* __restrict__ B,
                                                   long ldb, long b_tile_stride, int K, int nsub, lds_u8_t* smem,
                                                   bf16_t* C, const bf16_t* R, long ldc, const float* col_bias,
-                                                  int act) {
+                                                  int act, int a_touch_part = 0, int a_touch_parts = 0) {
   constexpr int FM = Cfg::FM, FN = Cfg::FN, NS = Cfg::kNS, BK = Cfg::kBK;
   const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
   const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
@@ -109,7 +109,14 @@ __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, 
 #pragma unroll
     for (int t = 0; t < Cfg::kMaxPer; ++t) {
       if (t + 1 < Cfg::kMaxPer || extra)
-        __builtin_amdgcn_global_load_lds((glb_u8_t*)src[t], stage + (t * Cfg::kNW + wave) * 1024, 16, 0, 0);
+        {
+          // A blocks (activations, re-read by every column tile of the model) keep the default policy;
+          // B blocks (weights, read exactly once per forward pass) take kWeightCpol
+          if (t * Cfg::kNW + wave < Cfg::kABlocks)
+            __builtin_amdgcn_global_load_lds((glb_u8_t*)src[t], stage + (t * Cfg::kNW + wave) * 1024, 16, 0, 0);
+          else
+            __builtin_amdgcn_global_load_lds((glb_u8_t*)src[t], stage + (t * Cfg::kNW + wave) * 1024, 16, 0, kWeightCpol);
+        }
       src[t] += last ? jump[t] : inc[t];
     }
     kt_issue = last ? 0 : kt_issue + 1;
@@ -144,6 +151,7 @@ __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, 
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
     if (s < total) issue_stage(s);
+  touch_a_rows<Cfg>(A, lda, K, a_touch_part, a_touch_parts);
 
   int g = 0;
   for (int sub = 0; sub < nsub; ++sub) {

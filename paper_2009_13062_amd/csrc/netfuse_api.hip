@@ -406,6 +406,7 @@ nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const 
     a.sC0 = (long)cog * HoWo; a.sC1 = (long)Ctot_out * HoWo;
     a.rows = cog; a.cols = HoWo; a.K = Kdim; a.nz0 = M * g;
     L.nz1 = B;
+    L.weights_are_a = 1;
     a.ep.row_bias = bias; a.ep.row_scale = scale; a.ep.row_shift = shift;
     a.ep.row_vec_stride0 = cog; a.ep.row_vec_stride1 = 0;
     a.ep.act = act; a.ep.act_before_residual = 0;

@@ -28,6 +28,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+// Non-temporal 16-byte load for operands that are read once per forward pass (the weights of a matmul): they
+// then do not displace the activations that neighbouring operators exchange through the caches.
+typedef uint32_t nf_u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ldnt16(const void* p) {
+  const nf_u32x4_t v = __builtin_nontemporal_load((const nf_u32x4_t*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <typename T> __device__ __forceinline__ float load_f32(const T* p);
 template <> __device__ __forceinline__ float load_f32<float>(const float* p) { return *p; }
 template <> __device__ __forceinline__ float load_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }

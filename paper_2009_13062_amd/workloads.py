@@ -83,12 +83,13 @@ class EncoderStack:
 
 
 class ResNetForward:
-    """Bottleneck ResNet / ResNeXt forward on x[1, M*3, image, image] -> [1, M*C_last] (workloads 3, 4).
+    """Bottleneck ResNet / ResNeXt forward on x[batch, M*3, image, image] -> [batch, M*C_last]
+    (workloads 3, 4; ``batch`` images per model, the models' channels concatenated in every tensor).
     Inference batch norm enters every convolution as its per-channel scale/shift epilogue."""
 
     def __init__(self, spec, params: Dict[str, Dict[str, torch.Tensor]], M: int, dtype=torch.bfloat16,
-                 eps: float = 1e-5, device="cuda", _shared=None):
-        self.spec, self.M, self.eps = spec, M, eps
+                 eps: float = 1e-5, device="cuda", batch: int = 1, _shared=None):
+        self.spec, self.M, self.eps, self.batch = spec, M, eps, batch
         self.P = params
         if _shared is not None:
             self.fold, self.buf = _shared
@@ -97,9 +98,13 @@ class ResNetForward:
         for c in spec.convs():
             p = params[c.name]
             self.fold[c.name] = nf.bn_fold(p["gamma"], p["beta"], p["mean"], p["var"], eps=eps)
-        # activation buffers, one per op output
+        self.buf = self._buffers(M, batch, dtype, device)
+
+    def _buffers(self, M, batch, dtype, device):
+        """Activation buffers, one per op output."""
+        spec = self.spec
         self.buf = {}
-        e = lambda ch, hw: torch.empty((1, M * ch, hw, hw), dtype=dtype, device=device)
+        e = lambda ch, hw: torch.empty((batch, M * ch, hw, hw), dtype=dtype, device=device)
         hw = nf.conv_out_size(spec.image, 7, 2, 3)
         self.buf["stem"] = e(spec.stem.cout, hw)
         hw = (hw + 2 - 3) // 2 + 1
@@ -112,14 +117,15 @@ class ResNetForward:
                 self.buf[blk.down.name] = e(blk.down.cout, hw2)
             self.buf[blk.conv3.name] = e(blk.conv3.cout, hw2)
             hw = hw2
-        self.buf["avgpool"] = torch.empty((1, M * spec.out_channels), dtype=dtype, device=device)
+        self.buf["avgpool"] = torch.empty((batch, M * spec.out_channels), dtype=dtype, device=device)
+        return self.buf
 
     @classmethod
-    def from_numpy(cls, inp, spec, M, dtype=torch.bfloat16, eps=1e-5):
+    def from_numpy(cls, inp, spec, M, dtype=torch.bfloat16, eps=1e-5, batch=1):
         params = {}
         for name, p in inp["params"].items():
             params[name] = {k: to_device(v, dtype if k == "w" else torch.float32) for k, v in p.items()}
-        return cls(spec, params, M, dtype, eps)
+        return cls(spec, params, M, dtype, eps, batch=batch)
 
     def _conv(self, x, c, act, residual=None):
         scale, shift = self.fold[c.name]
@@ -138,22 +144,32 @@ class ResNetForward:
         return nf.avgpool_global(x, out=self.buf["avgpool"])
 
     def per_model(self):
+        """M single-model instances on model m's weight slices.  With one image per model a model's
+        channels of every activation are one contiguous run, so the instances work in place on slices
+        of the merged buffers; with more, the batch stride separates them and each instance gets
+        buffers of its own."""
         out = []
         M = self.M
+        any_buf = next(iter(self.buf.values()))
         for m in range(M):
             P, fold, buf = {}, {}, {}
             for c in self.spec.convs():
                 sl = slice(m * c.cout, (m + 1) * c.cout)
                 P[c.name] = {"w": self.P[c.name]["w"][sl]}
                 fold[c.name] = (self.fold[c.name][0][sl], self.fold[c.name][1][sl])
-            for k, v in self.buf.items():
-                ch = v.shape[1] // M
-                buf[k] = v[:, m * ch:(m + 1) * ch]
-            out.append(ResNetForward(self.spec, P, 1, eps=self.eps, _shared=(fold, buf)))
+            one = ResNetForward(self.spec, P, 1, eps=self.eps, batch=self.batch, _shared=(fold, buf))
+            if self.batch == 1:
+                for k, v in self.buf.items():
+                    ch = v.shape[1] // M
+                    buf[k] = v[:, m * ch:(m + 1) * ch]
+            else:
+                one.buf = one._buffers(1, self.batch, any_buf.dtype, any_buf.device)
+            out.append(one)
         return out
 
     def slice_input(self, x, m):
-        return x[:, 3 * m:3 * (m + 1)]
+        """Model m's images [batch, 3, H, W] (a copy when the batch stride makes the slice non-contiguous)."""
+        return x[:, 3 * m:3 * (m + 1)].contiguous()
 
 
 class TinyLayer:

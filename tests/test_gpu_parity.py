@@ -464,6 +464,7 @@ def test_encoder_layer_workload2_full_size(nf, oracle):
     ref = OM.encoder_stack(inp, M, 1, shape.seq, shape.heads, out_bf16=True)
     err = np.abs(host(out) - ref)
     # end to end the two chains round differently at every call; LN output is O(1)
+    print("end-to-end max abs err %.4f mean %.5f" % (float(err.max()), float(err.mean())))
     assert float(err.max()) < 0.15 and float(err.mean()) < 0.01, (float(err.max()), float(err.mean()))
 
 
@@ -479,7 +480,7 @@ def test_encoder_stack_workload5_full_size_sampled(nf, oracle, seq):
     trace = []
     out = enc.forward(inp["X"], trace)
     assert torch.isfinite(out.float()).all()
-    sample = [0, 13, 31] if seq == 128 else [31]
+    sample = [0, 13, 31]
     for li in (0, 11):
         X_in = inp["X"] if li == 0 else trace[li - 1]["x2"]
         _encoder_per_call_parity(oracle, trace[li], X_in, _slice_layer(enc.layers[li], sample, shape.hidden),
@@ -547,6 +548,54 @@ def test_resnet_reduced(nf, oracle, card, bw):
         assert torch.equal(one.forward(net.slice_input(x, m)), out[:, m * spec.out_channels:(m + 1) * spec.out_channels])
 
 
+@pytest.mark.parametrize("batch", [2, 4])
+@pytest.mark.parametrize("card,bw", [(1, 64), (8, 8)], ids=["resnet", "resnext"])
+def test_resnet_reduced_batch_per_model(nf, oracle, card, bw, batch):
+    """Several images per model (Section 5.2's batch-size experiment): tensors are [batch, M*C, H, W], so a
+    model's channels are no longer one contiguous run.  Every op for every model against the oracle, the
+    chain end to end, and merged == one model at a time bit for bit."""
+    from oracle import models as OM
+    from paper_2009_13062_amd.workloads import ResNetForward
+    M = 3
+    spec = NI.resnet_spec(cardinality=card, base_width=bw, image=64, width_div=2, depths=(1, 1, 1, 1))
+    inp = NI.resnet_params(spec, M, bf16=True, batch=batch)
+    net = ResNetForward.from_numpy(inp, spec, M, batch=batch)
+    x = dev(inp["x"], torch.bfloat16)
+    out = net.forward(x)
+    assert out.shape == (batch, M * spec.out_channels)
+    _resnet_per_call_parity(oracle, net, x, spec, list(range(M)))
+    ref = OM.resnet_forward(inp, spec, M, out_bf16=True)
+    err = np.abs(host(out) - ref)
+    print("end-to-end max abs err %.4f (max |ref| %.3f)" % (float(err.max()), float(np.abs(ref).max())))
+    assert float(err.max()) < 0.1 * max(1.0, float(np.abs(ref).max())), float(err.max())
+    for m, one in enumerate(net.per_model()):
+        assert torch.equal(one.forward(net.slice_input(x, m)), out[:, m * spec.out_channels:(m + 1) * spec.out_channels])
+
+
+@pytest.mark.parametrize("batch", [2, 4])
+def test_encoder_reduced_batch_per_model(nf, oracle, batch):
+    """Several sequences per model: N = batch * seq rows per matmul, attention per (model, sequence, head)."""
+    from oracle import models as OM
+    from paper_2009_13062_amd.workloads import EncoderStack
+    M = 3
+    shape = NI.EncoderShape(hidden=256, heads=4, ffn=512, layers=2, seq=96, batch=batch)
+    inp = NI.encoder_stack(M, shape, bf16=True)
+    enc = EncoderStack.from_numpy(inp, M, batch, shape.seq, shape.heads)
+    X = dev(inp["X"], torch.bfloat16)
+    trace = []
+    out = enc.forward(X, trace)
+    for li in range(shape.layers):
+        X_in = X if li == 0 else trace[li - 1]["x2"]
+        _encoder_per_call_parity(oracle, trace[li], X_in, _slice_layer(enc.layers[li], list(range(M)), shape.hidden),
+                                 list(range(M)), batch, shape.seq, shape.heads, torch.bfloat16)
+    ref = OM.encoder_stack(inp, M, batch, shape.seq, shape.heads, out_bf16=True)
+    err = np.abs(host(out) - ref)
+    print("end-to-end max abs err %.4f mean %.5f" % (float(err.max()), float(err.mean())))
+    assert float(err.max()) < 0.15 and float(err.mean()) < 0.01
+    for m, one in enumerate(enc.per_model()):
+        assert torch.equal(one.forward(X[m:m + 1])[0], out[m])
+
+
 @pytest.mark.parametrize("name,M,card,bw,cfg", [("resnet50", 32, 1, 64, 3), ("resnext50_32x4d", 16, 32, 4, 4)])
 def test_resnet_full_size_sampled(nf, oracle, name, M, card, bw, cfg):
     """Workloads 3 and 4 at full size (224x224, M = 32 / 16, merged groups 32 / 512 on the 3x3 convs):
@@ -558,7 +607,7 @@ def test_resnet_full_size_sampled(nf, oracle, name, M, card, bw, cfg):
     net = ResNetForward(spec, inp["params"], M)
     out = net.forward(inp["x"])
     assert torch.isfinite(out.float()).all()
-    _resnet_per_call_parity(oracle, net, inp["x"], spec, [M - 1])
+    _resnet_per_call_parity(oracle, net, inp["x"], spec, [0, M // 2, M - 1])
 
 
 # ------------------------------------------------------------------ degenerate and extreme shapes
