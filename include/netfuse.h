@@ -83,6 +83,19 @@ nf_status netfuse_linear_packed(const void* X, const void* Wp, const float* bias
                                 nf_act act, void* stream);
 
 /*
+ * Ragged merged matmul: the per-task output layers of fine-tuned models have a different number of
+ * outputs per model (Section 5.1 leaves them unmerged for that reason; Section 6, common backbones).
+ * They still pair each weight set with its own input only, so they run as ONE launch over the models:
+ *   Y_m = act(X_m . W_m + bias_m),   X[M][N][K],   W_m[K][nout[m]],   bias_m[nout[m]],   Y_m[N][nout[m]]
+ * W, bias and Y are the per-model blocks concatenated in model order, each block dense row-major (so
+ * W_m starts K * (nout[0] + ... + nout[m-1]) elements into W, Y_m N times that sum into Y).
+ * nout is a HOST array of M positive ints, read during the call.  bias float or NULL.
+ * NF_EUNSUPPORTED for more than 256 models.
+ */
+nf_status netfuse_linear_ragged(const void* X, const void* W, const float* bias, void* Y, int M, int N,
+                                int K, const int* nout, nf_dtype dt, nf_act act, void* stream);
+
+/*
  * Merged convolution = grouped convolution with M*g groups (Section 3.1, "Convolution" and
  * "Operations with input-weight local computations"; Appendix A Eq. 2-6).  Inputs and weights
  * are concatenated along the channel dimension: x[Cin*m + ci] = x_m[ci], w[Cout*m + co] =

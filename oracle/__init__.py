@@ -75,6 +75,17 @@ def linear(X, W, bias=None, residual=None, act=ACT_NONE, out_bf16=False):
     return Y
 
 
+def linear_ragged(X, Ws, biases=None, act=ACT_NONE, out_bf16=False):
+    """Per-model output widths (the unmerged per-task heads of Section 5.1): the plain definition, model by
+    model -- Y_m = act(X[m] @ Ws[m] + biases[m]) with Ws[m] of shape [K, nout_m].  Returns the list of Y_m."""
+    X = _f32(X)
+    out = []
+    for m, Wm in enumerate(Ws):
+        b = None if biases is None else _f32(biases[m])[None]
+        out.append(linear(X[m:m + 1], _f32(Wm)[None], bias=b, act=act, out_bf16=out_bf16)[0])
+    return out
+
+
 def conv2d(x, w, M, g=1, bias=None, scale=None, shift=None, residual=None, stride=1, pad=0,
            dil=1, act=ACT_NONE, out_bf16=False):
     """x[B, M*Cin, H, W], w[M*Cout, Cin/g, KH, KW] -> y[B, M*Cout, Ho, Wo]; groups = M*g."""

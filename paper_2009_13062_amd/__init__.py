@@ -27,7 +27,8 @@ MERGE_BATCH, MERGE_CHANNEL = 0, 1
 EXPORTS = ("netfuse_linear", "netfuse_conv2d", "netfuse_layernorm", "netfuse_batchnorm",
            "netfuse_bn_fold", "netfuse_attention", "netfuse_maxpool2d", "netfuse_avgpool_global",
            "netfuse_merge_transpose", "netfuse_linear_pack_weight", "netfuse_linear_packed",
-           "netfuse_time_next_launch", "netfuse_linear_packed_panel", "netfuse_strerror")
+           "netfuse_time_next_launch", "netfuse_linear_packed_panel", "netfuse_linear_ragged",
+           "netfuse_strerror")
 
 
 class NetFuseError(RuntimeError):
@@ -56,6 +57,7 @@ def _load() -> ctypes.CDLL:
     lib.netfuse_linear_pack_weight.argtypes = [vp, vp, i, i, i, i, i, vp]
     lib.netfuse_linear_packed.argtypes = [vp, vp, fp, vp, vp, i, i, i, i, i, i, i, vp]
     lib.netfuse_time_next_launch.argtypes = [vp, vp]
+    lib.netfuse_linear_ragged.argtypes = [vp, vp, fp, vp, i, i, i, ctypes.POINTER(ctypes.c_int), i, i, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.netfuse_strerror.argtypes = [ctypes.c_int]
@@ -138,6 +140,29 @@ def linear_packed(X, Wp, panel, bias=None, residual=None, act=ACT_NONE, out=None
         _ptr(X), _ptr(Wp, X), _ptr(bias, f32=True), _ptr(residual, X), _ptr(Y, X), M, N, K, Nout,
         int(panel), _dt(X), int(act), _stream(stream)))
     return Y
+
+
+def linear_ragged(X, W, nout, bias=None, act=ACT_NONE, out=None, stream=None):
+    """Per-model output widths: X[M,N,K]; W flat = concat of W_m[K, nout[m]]; bias flat float32 = concat of
+    b_m[nout[m]] -> Y flat = concat of Y_m[N, nout[m]] (views: ragged_views)."""
+    M, N, K = X.shape
+    nout = [int(n) for n in nout]
+    if len(nout) != M or W.numel() != K * sum(nout):
+        raise ValueError("W must hold K * sum(nout) elements, nout one entry per model")
+    Y = torch.empty(N * sum(nout), dtype=X.dtype, device=X.device) if out is None else out
+    arr = (ctypes.c_int * M)(*nout)
+    _check("netfuse_linear_ragged", lib.netfuse_linear_ragged(
+        _ptr(X), _ptr(W, X), _ptr(bias, f32=True), _ptr(Y, X), M, N, K, arr, _dt(X), int(act), _stream(stream)))
+    return Y
+
+
+def ragged_views(flat, rows, nout):
+    """The per-model [rows, nout[m]] views of a ragged concatenation."""
+    out, o = [], 0
+    for n in nout:
+        out.append(flat[o:o + rows * n].view(rows, n))
+        o += rows * n
+    return out
 
 
 def time_next_launch(start_event, stop_event):

@@ -6,6 +6,61 @@
 
 namespace nf {
 
+// Ragged merged matmul: per-model output widths (the per-task classification heads, Section 5.1).
+// One workgroup = (model, 8 rows, 64 columns); its 4 wavefronts split K, each lane owns one column and 8
+// rows, so a wavefront reads 64 consecutive weights of a k row (coalesced, any alignment) and the
+// activations as wave-uniform broadcasts; the four partial sums meet in LDS.  The model of a workgroup is
+// found from the prefix sums of the per-model tile counts, which travel in the kernel arguments.
+constexpr int kRaggedMaxModels = 256;
+struct RaggedTable {
+  int tile_start[kRaggedMaxModels + 1];   // first workgroup of model m (prefix sum of rows tiles x column tiles)
+  int col_start[kRaggedMaxModels + 1];    // first output column of model m in the concatenation (prefix sum of nout)
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void linear_ragged_kernel(const T* __restrict__ X, const T* __restrict__ W,
+                                                           const float* __restrict__ bias, T* __restrict__ Y, int M,
+                                                           int N, int K, int act, RaggedTable tab) {
+  __shared__ float part[4][8][64];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  // binary search: the last model whose first tile is <= blockIdx.x
+  int lo = 0, hi = M - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) / 2;
+    if (tab.tile_start[mid] <= (int)blockIdx.x) lo = mid; else hi = mid - 1;
+  }
+  const int m = lo;
+  const int nout = tab.col_start[m + 1] - tab.col_start[m];
+  const int tiles_n = (nout + 63) / 64;
+  const int t = blockIdx.x - tab.tile_start[m];
+  const int row0 = (t / tiles_n) * 8, col = (t % tiles_n) * 64 + lane;
+  const T* Xm = X + ((size_t)m * N + row0) * K;
+  const T* Wm = W + (size_t)tab.col_start[m] * K;          // model m's [K][nout] block of the concatenation
+  const int rows = min(8, N - row0);
+  float acc[8] = {};
+  const int kper = (K + 3) / 4, k0 = wave * kper, k1 = min(K, k0 + kper);
+  if (col < nout) {
+    for (int k = k0; k < k1; ++k) {
+      const float w = load_f32(Wm + (size_t)k * nout + col);
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+        if (r < rows) acc[r] = fmaf(load_f32(Xm + (size_t)r * K + k), w, acc[r]);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 8; ++r) part[wave][r][lane] = acc[r];
+  __syncthreads();
+  // 512 outputs, 256 threads: two each; the k slices are added in order
+  for (int o = threadIdx.x; o < 8 * 64; o += 256) {
+    const int r = o / 64, c = (t % tiles_n) * 64 + o % 64;
+    if (r >= rows || c >= nout) continue;
+    float v = ((part[0][r][o % 64] + part[1][r][o % 64]) + part[2][r][o % 64]) + part[3][r][o % 64];
+    if (bias) v += bias[tab.col_start[m] + c];
+    v = apply_act(v, act);
+    store_f32(Y + (size_t)tab.col_start[m] * N + (size_t)(row0 + r) * nout + c, v);
+  }
+}
+
 // Merged matmul (Section 3.1): one 64x64 output tile of one model per workgroup; the model
 // index is folded into the grid.  256 threads, 4x4 outputs each, K in steps of 16 through LDS.
 template <typename T>

@@ -362,6 +362,40 @@ nf_status netfuse_linear_packed(const void* X, const void* Wp, const float* bias
   return launch_gemm_dma_packed(d, L, (hipStream_t)stream);
 }
 
+nf_status netfuse_linear_ragged(const void* X, const void* W, const float* bias, void* Y, int M, int N, int K,
+                                const int* nout, nf_dtype dt, nf_act act, void* stream) {
+  if (!X || !W || !Y || !nout) return NF_EINVAL;
+  if (M <= 0 || N <= 0 || K <= 0) return NF_EINVAL;
+  if (!is_dtype(dt) || !is_act(act)) return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(X, esz) || !aligned(W, esz) || !aligned(Y, esz) || !aligned(bias, 4)) return NF_EINVAL;
+  if (prod({M, N, K}) >= kMaxElems) return NF_EINVAL;
+  long long cols = 0, tiles = 0;
+  for (int m = 0; m < M; ++m) {
+    if (nout[m] <= 0) return NF_EINVAL;
+    cols += nout[m];
+    tiles += (long long)((N + 7) / 8) * ((nout[m] + 63) / 64);
+    if (cols > INT_MAX || tiles > kMaxGrid) return NF_EINVAL;
+  }
+  if (prod({cols, K}) >= kMaxElems || prod({cols, N}) >= kMaxElems) return NF_EINVAL;
+  if (M > kRaggedMaxModels) return NF_EUNSUPPORTED;
+  RaggedTable tab;
+  tab.tile_start[0] = 0; tab.col_start[0] = 0;
+  for (int m = 0; m < M; ++m) {
+    tab.tile_start[m + 1] = tab.tile_start[m] + ((N + 7) / 8) * ((nout[m] + 63) / 64);
+    tab.col_start[m + 1] = tab.col_start[m] + nout[m];
+  }
+  for (int m = M + 1; m <= kRaggedMaxModels; ++m) { tab.tile_start[m] = tab.tile_start[M]; tab.col_start[m] = tab.col_start[M]; }
+  hipStream_t s = (hipStream_t)stream;
+  if (dt == NF_F32)
+    nf_launch(linear_ragged_kernel<float>, dim3((unsigned)tiles), dim3(256), 0, s, (const float*)X, (const float*)W,
+              bias, (float*)Y, M, N, K, (int)act, tab);
+  else
+    nf_launch(linear_ragged_kernel<bf16_t>, dim3((unsigned)tiles), dim3(256), 0, s, (const bf16_t*)X, (const bf16_t*)W,
+              bias, (bf16_t*)Y, M, N, K, (int)act, tab);
+  return launched();
+}
+
 nf_status netfuse_conv2d(const void* x, const void* w, const float* bias, const float* scale, const float* shift,
                          const void* residual, void* y, int M, int B, int Cin, int Cout, int g, int H, int W,
                          int KH, int KW, int stride, int pad, int dilation, nf_dtype dt, nf_act act,

@@ -85,6 +85,20 @@ def test_packed_linear_rejects_bad_arguments(lib):
     assert width(32, 128, 768, 3072, 0) == 0 and width(32, 100, 768, 3072, 1) == 0 and width(0, 128, 768, 768, 1) == 0
 
 
+def test_ragged_linear_rejects_bad_arguments(lib):
+    import ctypes
+    f = lib.netfuse_linear_ragged
+    arr = lambda *v: (ctypes.c_int * len(v))(*v)
+    assert f(None, P, None, P, 2, 4, 8, arr(3, 5), 1, 0, None) == EINVAL
+    assert f(P, P, None, P, 2, 4, 8, None, 1, 0, None) == EINVAL
+    assert f(P, P, None, P, 2, 4, 8, arr(3, 0), 1, 0, None) == EINVAL          # a model without outputs
+    assert f(P, P, None, P, 2, 0, 8, arr(3, 5), 1, 0, None) == EINVAL
+    assert f(P, P, None, P, 2, 4, 8, arr(3, 5), 4, 0, None) == EINVAL
+    assert f(P, P, None, P, 2, 4, 8, arr(3, 5), 1, 9, None) == EINVAL
+    assert f(P, P + 1, None, P, 2, 4, 8, arr(3, 5), 1, 0, None) == EINVAL
+    assert f(P, P, None, P, 300, 4, 8, arr(*([3] * 300)), 1, 0, None) == 2     # more models than the table holds
+
+
 def test_conv_rejects_bad_arguments(lib):
     f = lib.netfuse_conv2d
     ok = dict(x=P, w=P, bias=None, scale=None, shift=None, res=None, y=P, M=2, B=1, Cin=8, Cout=8, g=2, H=8,

@@ -113,6 +113,37 @@ def test_linear(nf, oracle, case, dtype):
     check(host(got), ref, dtype, "linear %s" % (case,))
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=ids)
+@pytest.mark.parametrize("M,N,K,nout", [
+    (5, 3, 100, [10, 1000, 2, 65, 64]),            # widths around the 64-column tile, a one-tile and a 16-tile model
+    (32, 1, 768, None),                            # one sequence per model, encoder heads of 2..20 classes
+    (16, 9, 2048, [1000, 10, 100, 1] * 4),         # ResNet heads, two row tiles, a single-output model
+    (1, 8, 33, [7]),                               # one model
+], ids=["mixed", "encoder-heads", "resnet-heads", "single"])
+def test_linear_ragged(nf, oracle, M, N, K, nout, dtype):
+    """The per-task output layers (a different width per model) as one launch: every model against the
+    oracle's per-model definition, and nothing written outside a model's block."""
+    bf = dtype == torch.bfloat16
+    if nout is None:
+        nout = [int(v) for v in rng.integers(2, 21, M)]
+    X = grid(rnd(M, N, K), dtype)
+    Ws = [grid(rnd(K, n, std=K ** -0.5), dtype) for n in nout]
+    bs = [rnd(n, std=0.5) for n in nout]
+    ref = oracle.linear_ragged(X, Ws, bs, act=1, out_bf16=bf)
+    Wd = dev(np.concatenate([w.ravel() for w in Ws]), dtype)
+    bd = dev(np.concatenate(bs))
+    Y = nf.linear_ragged(dev(X, dtype), Wd, nout, bias=bd, act=1)
+    for m, y in enumerate(nf.ragged_views(Y, N, nout)):
+        check(host(y), ref[m], dtype, "ragged model %d (%d outputs)" % (m, nout[m]))
+    # without bias and activation, poisoned neighbours: model 1 (or 0) stays bit-identical
+    keep = min(1, M - 1)
+    clean = nf.linear_ragged(dev(X, dtype), Wd, nout)
+    Xp = X.copy()
+    Xp[[m for m in range(M) if m != keep]] = np.nan
+    dirty = nf.linear_ragged(dev(Xp, dtype), Wd, nout)
+    assert torch.equal(nf.ragged_views(clean, N, nout)[keep], nf.ragged_views(dirty, N, nout)[keep])
+
+
 def test_linear_residual_may_alias_output(nf, oracle):
     M, N, K, Nout = 2, 150, 128, 256
     X, W, R = (NI.on_bf16_grid(a) for a in (rnd(M, N, K), rnd(M, K, Nout, std=0.1), rnd(M, N, Nout)))

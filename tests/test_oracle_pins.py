@@ -489,3 +489,24 @@ def test_network_shape_tables():
     assert widths == [128, 256, 512, 1024]
     assert all(c.groups == 32 for c in x50.convs() if c.k == 3)
     assert sorted({c.cin // c.groups for c in x50.convs() if c.k == 3}) == [4, 8, 16, 32]
+
+
+# ------------------------------------------------------------------ ragged per-task heads
+def test_linear_ragged_is_the_per_model_definition(oracle):
+    """Per-model output widths: against a numpy float64 product per model, and against the uniform-width
+    operator when all widths agree."""
+    r = np.random.default_rng(5)
+    M, N, K = 4, 3, 37
+    nout = [1, 10, 65, 7]
+    X = r.standard_normal((M, N, K)).astype(np.float32)
+    Ws = [r.standard_normal((K, n)).astype(np.float32) for n in nout]
+    bs = [r.standard_normal(n).astype(np.float32) for n in nout]
+    got = oracle.linear_ragged(X, Ws, bs, act=oracle.ACT_RELU)
+    for m in range(M):
+        want = np.maximum(X[m].astype(np.float64) @ Ws[m].astype(np.float64) + bs[m], 0.0)
+        assert got[m].shape == (N, nout[m])
+        np.testing.assert_allclose(got[m], want, rtol=1e-6, atol=1e-6)
+    same = [r.standard_normal((K, 6)).astype(np.float32) for _ in range(M)]
+    uni = oracle.linear(X, np.stack(same))
+    for m, y in enumerate(oracle.linear_ragged(X, same)):
+        assert np.array_equal(y, uni[m])
