@@ -82,6 +82,41 @@ class EncoderStack:
         return out
 
 
+def encoder_call_list(layers: int):
+    """The calls of EncoderStack.forward as data: (entry point, operation, producer of the input, producer of
+    the residual or None, activation), operations and producers named as in netfuse_inputs.graphs."""
+    out, x = [], "x"
+    for L in range(layers):
+        p = "l%d." % L
+        out += [("linear", p + "qkv", x, None, nf.ACT_NONE),
+                ("attention", p + "attention", p + "qkv", None, nf.ACT_NONE),
+                ("linear", p + "o", p + "attention", x, nf.ACT_NONE),
+                ("layernorm", p + "ln1", p + "o", None, nf.ACT_NONE),
+                ("linear", p + "ffn1", p + "ln1", None, nf.ACT_GELU),
+                ("linear", p + "ffn2", p + "ffn1", p + "ln1", nf.ACT_NONE),
+                ("layernorm", p + "ln2", p + "ffn2", None, nf.ACT_NONE)]
+        x = p + "ln2"
+    return out
+
+
+def resnet_call_list(spec):
+    """The calls of ResNetForward.forward as data (see encoder_call_list); every conv2d carries its folded
+    batch normalisation."""
+    out = [("conv2d", "stem", "x", None, nf.ACT_RELU), ("maxpool2d", "maxpool", "stem", None, nf.ACT_NONE)]
+    x = "maxpool"
+    for blk in spec.blocks:
+        out.append(("conv2d", blk.conv1.name, x, None, nf.ACT_RELU))
+        out.append(("conv2d", blk.conv2.name, blk.conv1.name, None, nf.ACT_RELU))
+        sc = x
+        if blk.down is not None:
+            out.append(("conv2d", blk.down.name, x, None, nf.ACT_NONE))
+            sc = blk.down.name
+        out.append(("conv2d", blk.conv3.name, blk.conv2.name, sc, nf.ACT_RELU))
+        x = blk.conv3.name
+    out.append(("avgpool_global", "avgpool", x, None, nf.ACT_NONE))
+    return out
+
+
 class ResNetForward:
     """Bottleneck ResNet / ResNeXt forward on x[batch, M*3, image, image] -> [batch, M*C_last]
     (workloads 3, 4; ``batch`` images per model, the models' channels concatenated in every tensor).
