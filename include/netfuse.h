@@ -160,6 +160,23 @@ nf_status netfuse_attention(const void* Q, const void* K, const void* V, const f
                             float scale, nf_dtype dt, void* stream);
 
 /*
+ * Merged relative-position attention (the "extra computations" of XLNet that Section 5.2 refers to;
+ * the paper gives no equations, so this is the published Transformer-XL / XLNet form).  As
+ * netfuse_attention, with a position term and per-model, per-head bias vectors added to the query:
+ *   s_ij = scale * ( (Q_i + bias_w) . K_j  +  (Q_i + bias_r) . Kr[S - i + j] ) + mask_j
+ * Kr[M][2 S][heads*d] (storage type of Q, dense): row p of model m is ITS projection of the encoding of
+ * relative distance S - p, i.e. what netfuse_linear gives for the 2 S sinusoid rows of distances
+ * S, S-1, ..., -S+1 and that model's position weights; rows 1 ... 2S-1 are used.  This indexing is
+ * the "relative shift" of those models written out.  bias_w, bias_r: float[M][heads*d] or NULL.
+ * A segment term that is constant over the keys of a query (single-segment inputs) cancels in the
+ * softmax and is not part of this call.
+ */
+nf_status netfuse_attention_relpos(const void* Q, const void* K, const void* V, const void* Kr,
+                                   const float* bias_w, const float* bias_r, const float* mask, void* O,
+                                   int M, int B, int S, int heads, int d, long stride_m, long stride_row,
+                                   float scale, nf_dtype dt, void* stream);
+
+/*
  * Non-trainable operators merge by concatenation (Section 3.1, "Non-trainable operations"), so
  * these act per channel of the channel-merged tensor; Ctot = M*C.
  * Max pooling: x[B][Ctot][H][W] -> y[B][Ctot][Ho][Wo], window k x k, Ho = (H + 2 pad - k)/stride + 1;

@@ -204,3 +204,41 @@ def merge_transpose(src, M, to_channel):
         dst = np.empty((M, rows, H), np.float32)
     _load().oracle_merge_transpose(_p(src), _p(dst), M, rows, H, int(bool(to_channel)))
     return dst
+
+
+def attention_relpos_packed(qkv, Kr, B, S, heads, bias_w=None, bias_r=None, scale=None, mask=None, out_bf16=False):
+    """Relative-position attention (Transformer-XL / XLNet form; the reference paper gives no equations for
+    it, so no pin comes from there) written out per (model, sequence, head, query) in float64:
+      s_ij = scale * ((q_i + bias_w) . k_j + (q_i + bias_r) . Kr[m, S - i + j]) + mask_j,  p = softmax_j,  o_i = sum_j p_ij v_j
+    qkv[M, B*S, 3*heads*d] with column blocks [Q | K | V]; Kr[M, 2S, heads*d]; biases [M, heads*d]."""
+    qkv, Kr = _f32(qkv).astype(np.float64), _f32(Kr).astype(np.float64)
+    M, N, th = qkv.shape
+    Hd = th // 3
+    d = Hd // heads
+    assert N == B * S and Kr.shape == (M, 2 * S, Hd)
+    scale = d ** -0.5 if scale is None else scale
+    out = np.zeros((M, N, Hd), np.float64)
+    for m in range(M):
+        for b in range(B):
+            rows = slice(b * S, (b + 1) * S)
+            for h in range(heads):
+                c = slice(h * d, (h + 1) * d)
+                q, k, v = qkv[m, rows, c], qkv[m, rows, Hd:][:, c], qkv[m, rows, 2 * Hd:][:, c]
+                bw = 0.0 if bias_w is None else np.asarray(bias_w, np.float64)[m, c]
+                br = 0.0 if bias_r is None else np.asarray(bias_r, np.float64)[m, c]
+                for i in range(S):
+                    s = np.empty(S)
+                    for j in range(S):
+                        s[j] = scale * (np.dot(q[i] + bw, k[j]) + np.dot(q[i] + br, Kr[m, S - i + j, c]))
+                        if mask is not None:
+                            s[j] += mask[m, b, j]
+                    p = np.exp(s - s.max())
+                    out[m, b * S + i, c] = (p / p.sum()) @ v
+    out = out.astype(np.float32)
+    return round_bf16(out) if out_bf16 else out
+
+
+def round_bf16(a):
+    """One round-to-nearest-even to the bf16 grid, by the C oracle's own routine (a 1x1 identity matmul)."""
+    a = _f32(a)
+    return linear(a.reshape(1, -1, 1), np.ones((1, 1, 1), np.float32), out_bf16=True).reshape(a.shape)

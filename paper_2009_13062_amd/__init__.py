@@ -28,7 +28,7 @@ EXPORTS = ("netfuse_linear", "netfuse_conv2d", "netfuse_layernorm", "netfuse_bat
            "netfuse_bn_fold", "netfuse_attention", "netfuse_maxpool2d", "netfuse_avgpool_global",
            "netfuse_merge_transpose", "netfuse_linear_pack_weight", "netfuse_linear_packed",
            "netfuse_time_next_launch", "netfuse_linear_packed_panel", "netfuse_linear_ragged",
-           "netfuse_strerror")
+           "netfuse_attention_relpos", "netfuse_strerror")
 
 
 class NetFuseError(RuntimeError):
@@ -57,6 +57,7 @@ def _load() -> ctypes.CDLL:
     lib.netfuse_linear_pack_weight.argtypes = [vp, vp, i, i, i, i, i, vp]
     lib.netfuse_linear_packed.argtypes = [vp, vp, fp, vp, vp, i, i, i, i, i, i, i, vp]
     lib.netfuse_time_next_launch.argtypes = [vp, vp]
+    lib.netfuse_attention_relpos.argtypes = [vp, vp, vp, vp, fp, fp, fp, vp, i, i, i, i, i, l, l, f, i, vp]
     lib.netfuse_linear_ragged.argtypes = [vp, vp, fp, vp, i, i, i, ctypes.POINTER(ctypes.c_int), i, i, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
@@ -255,6 +256,26 @@ def attention(Q, K, V, B, S, heads, scale=None, mask=None, out=None, stream=None
     _check("netfuse_attention", lib.netfuse_attention(
         _ptr(Q), _ptr(K, Q), _ptr(V, Q), _ptr(mask, f32=True), _ptr(O, Q), M, B, S, heads, d, N * Hd,
         Hd, float(scale), _dt(Q), _stream(stream)))
+    return O
+
+
+def attention_relpos_packed(QKV, Kr, B, S, heads, bias_w=None, bias_r=None, scale=None, mask=None, out=None,
+                            stream=None):
+    """Relative-position attention on QKV[M, B*S, 3*heads*d] (column blocks [Q | K | V]) and the projected
+    position encodings Kr[M, 2*S, heads*d]; bias_w, bias_r float32 [M, heads*d]."""
+    M, N, three_h = QKV.shape
+    Hd = three_h // 3
+    d = Hd // heads
+    if N != B * S or three_h != 3 * heads * d or tuple(Kr.shape) != (M, 2 * S, Hd):
+        raise ValueError("QKV must be [M, B*S, 3*heads*d] and Kr [M, 2*S, heads*d]")
+    if scale is None:
+        scale = d ** -0.5
+    O = torch.empty((M, N, Hd), dtype=QKV.dtype, device=QKV.device) if out is None else out
+    base, esz = _ptr(QKV), QKV.element_size()
+    _check("netfuse_attention_relpos", lib.netfuse_attention_relpos(
+        base, base + Hd * esz, base + 2 * Hd * esz, _ptr(Kr, QKV), _ptr(bias_w, f32=True), _ptr(bias_r, f32=True),
+        _ptr(mask, f32=True), _ptr(O, QKV), M, B, S, heads, d, N * three_h, three_h, float(scale), _dt(QKV),
+        _stream(stream)))
     return O
 
 

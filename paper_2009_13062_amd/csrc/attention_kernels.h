@@ -80,6 +80,89 @@ __global__ __launch_bounds__(256) void attention_generic_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Relative-position attention (Transformer-XL / XLNet form), general kernel: as above, with the score
+//   s_ij = scale * ( (q_i + bias_w) . k_j  +  (q_i + bias_r) . kr[S - i + j] ) + mask_j
+// where kr[p] is the model's projected encoding of relative distance S - p (row p of Kr[M][2S][heads*d]).
+// The two biased copies of the query row sit in LDS; lane j walks its key row and its position row.
+// ------------------------------------------------------------------------------------------
+struct AttnRelArgs {
+  AttnArgs a;
+  const void* Kr;          // [M][2S][heads*d], storage type of Q
+  const float* bias_w;     // [M][heads*d] or null
+  const float* bias_r;     // [M][heads*d] or null
+};
+
+template <typename T, int DPL>
+__global__ __launch_bounds__(256) void attention_relpos_kernel(AttnRelArgs ra) {
+  const AttnArgs& a = ra.a;
+  __shared__ float qw[4][64 * DPL];
+  __shared__ float qr[4][64 * DPL];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const long wid = (long)blockIdx.x * 4 + wave;
+  const long total = (long)a.M * a.B * a.heads * a.S;
+  if (wid >= total) return;                       // uniform per wavefront
+  const int i = (int)(wid % a.S);
+  long t = wid / a.S;
+  const int h = (int)(t % a.heads);  t /= a.heads;
+  const int b = (int)(t % a.B);
+  const int m = (int)(t / a.B);
+  const long hd = (long)a.heads * a.d;
+  const T* Qp = (const T*)a.Q + (long)m * a.stride_m + ((long)b * a.S + i) * a.stride_row + (long)h * a.d;
+  const T* Kp = (const T*)a.K + (long)m * a.stride_m + ((long)b * a.S) * a.stride_row + (long)h * a.d;
+  const T* Vp = (const T*)a.V + (long)m * a.stride_m + ((long)b * a.S) * a.stride_row + (long)h * a.d;
+  const T* Rp = (const T*)ra.Kr + ((long)m * 2 * a.S + (a.S - i)) * hd + (long)h * a.d;     // row S - i + j at + j*hd
+  const float* mk = a.mask ? a.mask + ((long)m * a.B + b) * a.S : nullptr;
+#pragma unroll
+  for (int e = 0; e < DPL; ++e) {
+    const int tt = lane + 64 * e;
+    const float q = tt < a.d ? load_f32(Qp + tt) : 0.f;
+    qw[wave][tt] = tt < a.d ? q + (ra.bias_w ? ra.bias_w[m * hd + h * a.d + tt] : 0.f) : 0.f;
+    qr[wave][tt] = tt < a.d ? q + (ra.bias_r ? ra.bias_r[m * hd + h * a.d + tt] : 0.f) : 0.f;
+  }
+  __builtin_amdgcn_wave_barrier();
+  float mrun = -3.0e38f, lrun = 0.f, acc[DPL];
+#pragma unroll
+  for (int e = 0; e < DPL; ++e) acc[e] = 0.f;
+  for (int j0 = 0; j0 < a.S; j0 += 64) {
+    const int j = j0 + lane;
+    float s = -3.0e38f;
+    if (j < a.S) {
+      const T* kr = Kp + (long)j * a.stride_row;
+      const T* pr = Rp + (long)j * hd;
+      float ac = 0.f, bd = 0.f;
+      for (int tt = 0; tt < a.d; ++tt) {
+        ac = fmaf(qw[wave][tt], load_f32(kr + tt), ac);
+        bd = fmaf(qr[wave][tt], load_f32(pr + tt), bd);
+      }
+      s = (ac + bd) * a.scale + (mk ? mk[j] : 0.f);
+    }
+    const float mnew = fmaxf(mrun, wave_max(s));
+    const float p = j < a.S ? expf(s - mnew) : 0.f;
+    const float corr = expf(mrun - mnew);
+    lrun = lrun * corr + wave_sum(p);
+#pragma unroll
+    for (int e = 0; e < DPL; ++e) acc[e] *= corr;
+    const int nj = min(64, a.S - j0);
+    for (int jj = 0; jj < nj; ++jj) {
+      const float pj = __shfl(p, jj, kWave);
+      const T* vr = Vp + (long)(j0 + jj) * a.stride_row;
+#pragma unroll
+      for (int e = 0; e < DPL; ++e) {
+        const int tt = lane + 64 * e;
+        if (tt < a.d) acc[e] = fmaf(pj, load_f32(vr + tt), acc[e]);
+      }
+    }
+    mrun = mnew;
+  }
+  T* Op = (T*)a.O + (((long)m * a.B + b) * a.S + i) * hd + (long)h * a.d;
+#pragma unroll
+  for (int e = 0; e < DPL; ++e) {
+    const int tt = lane + 64 * e;
+    if (tt < a.d) store_f32(Op + tt, acc[e] / lrun);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // bf16 MFMA kernel for head dimension 64.
 //
 // Workgroup = 4 wavefronts = 128 query rows of one (model, sequence, head); wave w owns 32 of them.

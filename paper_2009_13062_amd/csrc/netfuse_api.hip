@@ -690,6 +690,44 @@ nf_status netfuse_attention(const void* Q, const void* K, const void* V, const f
   return launched();
 }
 
+nf_status netfuse_attention_relpos(const void* Q, const void* K, const void* V, const void* Kr, const float* bias_w,
+                                   const float* bias_r, const float* mask, void* O, int M, int B, int S, int heads,
+                                   int d, long stride_m, long stride_row, float scale, nf_dtype dt, void* stream) {
+  if (!Q || !K || !V || !Kr || !O) return NF_EINVAL;
+  if (M <= 0 || B <= 0 || S <= 0 || heads <= 0 || d <= 0) return NF_EINVAL;
+  if (!is_dtype(dt) || !(scale == scale)) return NF_EINVAL;
+  const long long hd = (long long)heads * d;
+  if (hd > INT_MAX || stride_row < hd) return NF_EINVAL;
+  if (prod({B, S}) > INT_MAX / 2) return NF_EINVAL;
+  if (stride_m < 0 || (M > 1 && stride_m < (long long)(B * (long long)S - 1) * stride_row + hd)) return NF_EINVAL;
+  if (prod({M, B, S, hd}) >= kMaxElems || prod({M, stride_m}) >= kMaxElems || prod({M, 2, S, hd}) >= kMaxElems)
+    return NF_EINVAL;
+  const size_t esz = dt == NF_F32 ? 4 : 2;
+  if (!aligned(Q, esz) || !aligned(K, esz) || !aligned(V, esz) || !aligned(Kr, esz) || !aligned(O, esz) ||
+      !aligned(mask, 4) || !aligned(bias_w, 4) || !aligned(bias_r, 4))
+    return NF_EINVAL;
+  if (d > 256) return NF_EUNSUPPORTED;
+  const long long waves = prod({M, B, heads, S});
+  const long long blocks = (waves + 3) / 4;
+  if (blocks > kMaxGrid) return NF_EUNSUPPORTED;
+  AttnRelArgs ra;
+  AttnArgs& a = ra.a;
+  a.Q = Q; a.K = K; a.V = V; a.mask = mask; a.O = O;
+  a.M = M; a.B = B; a.S = S; a.heads = heads; a.d = d;
+  a.stride_m = stride_m; a.stride_row = stride_row; a.scale = scale;
+  ra.Kr = Kr; ra.bias_w = bias_w; ra.bias_r = bias_r;
+  hipStream_t s = (hipStream_t)stream;
+  const int dpl = (d + 63) / 64;
+#define NF_ATTR(T, DPL) nf_launch((attention_relpos_kernel<T, DPL>), dim3((unsigned)blocks), dim3(256), 0, s, ra)
+  if (dt == NF_F32) {
+    if (dpl == 1) NF_ATTR(float, 1); else if (dpl == 2) NF_ATTR(float, 2); else NF_ATTR(float, 4);
+  } else {
+    if (dpl == 1) NF_ATTR(bf16_t, 1); else if (dpl == 2) NF_ATTR(bf16_t, 2); else NF_ATTR(bf16_t, 4);
+  }
+#undef NF_ATTR
+  return launched();
+}
+
 nf_status netfuse_maxpool2d(const void* x, void* y, int B, int Ctot, int H, int W, int k, int stride, int pad,
                             nf_dtype dt, void* stream) {
   if (!x || !y) return NF_EINVAL;

@@ -349,6 +349,29 @@ def test_attention(nf, oracle, dtype, M, B, S, heads, d, use_mask):
     assert torch.equal(got, got2), "packed and separate Q/K/V must agree bit for bit"
 
 
+@pytest.mark.parametrize("dtype,M,B,S,heads,d", [(torch.bfloat16, 2, 1, 48, 3, 64), (torch.bfloat16, 3, 2, 70, 2, 32),
+                                               (torch.float32, 2, 1, 33, 2, 16), (torch.float32, 1, 1, 5, 1, 80)],
+                         ids=lambda v: str(v).replace("torch.", ""))
+def test_attention_relpos(nf, oracle, dtype, M, B, S, heads, d):
+    """Relative-position attention (the XLNet / Transformer-XL score) per (model, sequence, head); with a zero
+    position term it is the plain merged attention; NaN in another model stays there."""
+    bf = dtype == torch.bfloat16
+    Hd = heads * d
+    qkv, Kr = grid(rnd(M, B * S, 3 * Hd), dtype), grid(rnd(M, 2 * S, Hd), dtype)
+    bw, br, mask = rnd(M, Hd, std=0.5), rnd(M, Hd, std=0.5), rnd(M, B, S, std=2.0)
+    ref = oracle.attention_relpos_packed(qkv, Kr, B, S, heads, bias_w=bw, bias_r=br, mask=mask, out_bf16=bf)
+    got = nf.attention_relpos_packed(dev(qkv, dtype), dev(Kr, dtype), B, S, heads, bias_w=dev(bw), bias_r=dev(br), mask=dev(mask))
+    check(host(got), ref, dtype, "relative-position attention")
+    plain = nf.attention_packed(dev(qkv, dtype), B, S, heads)
+    zero = nf.attention_relpos_packed(dev(qkv, dtype), dev(np.zeros_like(Kr), dtype), B, S, heads)
+    check(host(zero), host(plain), dtype, "zero position term")
+    if M > 1:
+        qp, kp = qkv.copy(), Kr.copy()
+        qp[1:], kp[1:] = np.nan, np.nan
+        dirty = nf.attention_relpos_packed(dev(qp, dtype), dev(kp, dtype), B, S, heads, bias_w=dev(bw), bias_r=dev(br), mask=dev(mask))
+        assert torch.equal(dirty[0], got[0]) and not torch.isfinite(dirty[1].float()).any()
+
+
 def test_attention_sharp_softmax(nf, oracle):
     """Large logits: the row maximum must be subtracted, and one key must win exactly."""
     M, S, heads, d = 2, 96, 2, 64

@@ -510,3 +510,61 @@ def test_linear_ragged_is_the_per_model_definition(oracle):
     uni = oracle.linear(X, np.stack(same))
     for m, y in enumerate(oracle.linear_ragged(X, same)):
         assert np.array_equal(y, uni[m])
+
+
+# ------------------------------------------------------------------ relative-position attention
+def _rel_shift_reference(qkv, Kr, S, heads, bias_w, bias_r, scale, mask):
+    """The same operator by the published procedure instead of the closed-form index: the raw position
+    scores against ALL 2S encodings (distances S, S-1, ..., -S+1), then XLNet's "relative shift": view the
+    [S, 2S] block as [2S, S], drop the first row, view the rest as [S, 2S-1], keep the first S columns."""
+    M, N, th = qkv.shape
+    Hd = th // 3
+    d = Hd // heads
+    out = np.zeros((M, N, Hd))
+    for m in range(M):
+        for h in range(heads):
+            c = slice(h * d, (h + 1) * d)
+            q, k, v = (qkv[m, :, i * Hd:(i + 1) * Hd][:, c].astype(np.float64) for i in range(3))
+            ac = (q + bias_w[m, c]) @ k.T
+            raw = (q + bias_r[m, c]) @ Kr[m, :, c].astype(np.float64).T                    # [S, 2S]
+            bd = raw.reshape(2 * S, S)[1:].reshape(S, 2 * S - 1)[:, :S]
+            s = scale * (ac + bd) + mask[m, 0][None, :]
+            p = np.exp(s - s.max(axis=1, keepdims=True))
+            out[m, :, c] = (p / p.sum(axis=1, keepdims=True)) @ v
+    return out
+
+
+def test_attention_relpos_against_the_relative_shift_procedure_and_special_cases(oracle):
+    """No number for this operator exists in the reference paper (it only says XLNet has extra computations):
+    the oracle is pinned to the Transformer-XL relative-shift procedure, to plain attention when the position
+    term vanishes, and to a distance-only closed form."""
+    M, S, heads, d = 2, 7, 2, 4
+    Hd = heads * d
+    qkv, Kr = rnd(M, S, 3 * Hd), rnd(M, 2 * S, Hd)
+    bw, br, mask = rnd(M, Hd), rnd(M, Hd), rnd(M, 1, S)
+    got = oracle.attention_relpos_packed(qkv, Kr, 1, S, heads, bias_w=bw, bias_r=br, scale=0.37, mask=mask)
+    close(got, _rel_shift_reference(qkv, Kr, S, heads, bw, br, 0.37, mask))
+    # no position term, no biases: the plain merged attention (pinned above against torch)
+    zero = np.zeros_like(Kr)
+    close(oracle.attention_relpos_packed(qkv, zero, 1, S, heads), oracle.attention_packed(qkv, 1, S, heads))
+    # bias_w alone adds bw.k_j to every row of scores; with identical keys that is a constant: no effect
+    same_k = qkv.copy()
+    same_k[:, :, Hd:2 * Hd] = same_k[:, :1, Hd:2 * Hd]
+    close(oracle.attention_relpos_packed(same_k, zero, 1, S, heads, bias_w=bw), oracle.attention_packed(same_k, 1, S, heads))
+    # Q = 0, K = 0, bias_r = e_0, Kr[p] = g(S - p) e_0: the weights depend on the distance i - j only
+    q0 = np.zeros_like(qkv)
+    q0[:, :, 2 * Hd:] = qkv[:, :, 2 * Hd:]
+    g = rnd(2 * S)
+    Krd = np.zeros_like(Kr)
+    Krd[:, :, 0::d] = g[None, :, None]
+    e0 = np.zeros((M, Hd), np.float32)
+    e0[:, 0::d] = 1.0
+    got = oracle.attention_relpos_packed(q0, Krd, 1, S, heads, bias_r=e0, scale=1.0)
+    for i in range(S):
+        w = np.exp(np.array([g[S - i + j] for j in range(S)], np.float64))
+        w /= w.sum()
+        close(got[0, i, :d], w @ q0[0, :, 2 * Hd:2 * Hd + d].astype(np.float64))
+    # two sequences per model are independent problems
+    two = np.concatenate([qkv, qkv[:, ::-1]], axis=1)
+    both = oracle.attention_relpos_packed(two, Kr, 2, S, heads, bias_w=bw, bias_r=br)
+    close(both[:, :S], oracle.attention_relpos_packed(qkv, Kr, 1, S, heads, bias_w=bw, bias_r=br))
