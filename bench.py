@@ -35,6 +35,8 @@ WORKLOADS = {
     "encoder12_m32_s512": ("encoder", 32, dict(layers=12, seq=512, cfg=5)),
     # 113 MB of weights would stay in the 256 MB memory-side cache: three weight copies are rotated
     "encoder1_m8_s128": ("encoder", 8, dict(layers=1, seq=128, cfg=2, rotate=3)),
+    # XLNet-shaped: the same stack with relative-position attention (one more matmul and a position term per layer)
+    "xlnet12_m32_s128": ("encoder", 32, dict(layers=12, seq=128, cfg=6, rel=True)),
     "resnet50_m32": ("resnet", 32, dict(card=1, bw=64, cfg=3)),
     "resnext50_32x4d_m16": ("resnet", 16, dict(card=32, bw=4, cfg=4)),
 }
@@ -128,6 +130,11 @@ class OpTimer:
             M, N, th = QKV.shape
             return "attention_S%d" % S, 4.0 * M * B * heads * S * S * (th // 3 // heads), QKV.element_size() * (QKV.numel() + y_.numel())
 
+        def d_attn_rel(y_, QKV, Kr, B, S, heads, **kw):
+            M, N, th = QKV.shape
+            return ("attention_relpos_S%d" % S, 6.0 * M * B * heads * S * S * (th // 3 // heads),
+                    QKV.element_size() * (QKV.numel() + Kr.numel() + y_.numel()))
+
         def d_ln(y_, x, gamma, beta, M, residual=None, **kw):
             return "layernorm_H%d" % (gamma.numel() // M), 8.0 * x.numel(), x.element_size() * x.numel() * 2 + 8 * gamma.numel()
 
@@ -140,6 +147,7 @@ class OpTimer:
         self._wrap("linear_packed", d_linear_packed)
         self._wrap("conv2d", d_conv)
         self._wrap("attention_packed", d_attn)
+        self._wrap("attention_relpos_packed", d_attn_rel)
         self._wrap("layernorm", d_ln)
         self._wrap("maxpool2d", d_pool("maxpool"))
         self._wrap("avgpool_global", d_pool("avgpool"))
@@ -211,9 +219,9 @@ def build_workload(name, torch, M=None, batch=1):
         rot = p.get("rotate", 1)
         nets, x = [], None
         for r in range(rot):
-            inp = encoder_stack_device(M, shape, cfg=p["cfg"] + 100 * r)
+            inp = encoder_stack_device(M, shape, cfg=p["cfg"] + 100 * r, rel=p.get("rel", False))
             nets.append(EncoderStack(inp["layers"], M, batch, shape.seq, shape.heads,
-                                     buffers=nets[0].buf if nets else None))
+                                     buffers=nets[0].buf if nets else None, R=inp.get("R")))
             x = inp["X"] if x is None else x
         cfg = dict(workload=name, M=M, layers=shape.layers, seq_len=shape.seq, hidden=shape.hidden,
                    heads=shape.heads, ffn=shape.ffn, batch_per_model=batch, weight_copies_rotated=rot)
@@ -474,7 +482,7 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=HEADLINE, choices=sorted(WORKLOADS))
-    ap.add_argument("--others", default="encoder12_m32_s512,resnet50_m32,resnext50_32x4d_m16,encoder1_m8_s128",
+    ap.add_argument("--others", default="encoder12_m32_s512,xlnet12_m32_s128,resnet50_m32,resnext50_32x4d_m16,encoder1_m8_s128",
                     help="comma list of further workloads reported under 'other_workloads' ('' = none)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")

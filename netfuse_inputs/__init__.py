@@ -109,11 +109,22 @@ ENCODER_LAYER_KEYS = ("Wqkv", "bqkv", "Wo", "bo", "ln1_g", "ln1_b", "W1", "b1", 
                       "ln2_g", "ln2_b")
 
 
+def relative_positions(seq: int, hidden: int) -> np.ndarray:
+    """The sinusoid encodings of the relative distances seq, seq-1, ..., -seq+1 (an input tensor of the
+    relative-position attention, shared by all models): row p = [sin(pos f_0..), cos(pos f_0..)] for
+    pos = seq - p and f_i = 10000^(-2i/hidden)."""
+    pos = np.arange(seq, -seq, -1, dtype=np.float64)
+    inv = 1.0 / (10000.0 ** (np.arange(0, hidden, 2, dtype=np.float64) / hidden))
+    ang = pos[:, None] * inv[None, :]
+    return np.concatenate([np.sin(ang), np.cos(ang)], axis=1).astype(np.float32)
+
+
 def encoder_stack(M: int, shape: EncoderShape, cfg: int = 2, bf16: bool = True,
-                  order: Optional[List[int]] = None) -> Dict[str, object]:
+                  order: Optional[List[int]] = None, rel: bool = False) -> Dict[str, object]:
     """Post-LN encoder layers: X[M, batch*seq, hidden] ~ N(0,1); weights/biases ~ N(0,0.02);
     LayerNorm gamma ~ 1+N(0,0.02), beta ~ N(0,0.02).  Returns {"X":..., "layers":[{key: merged}]}.
-    Wqkv has column blocks [Q | K | V]."""
+    Wqkv has column blocks [Q | K | V].  rel: also the parameters of relative-position attention per layer
+    (position projection Wr[hidden, hidden], query biases rwb, rrb ~ N(0,0.02)) and "R" = relative_positions."""
     order = list(range(M)) if order is None else list(order)
     Hd, F = shape.hidden, shape.ffn
     xs, per_layer = [], [dict((k, []) for k in ENCODER_LAYER_KEYS) for _ in range(shape.layers)]
@@ -134,6 +145,10 @@ def encoder_stack(M: int, shape: EncoderShape, cfg: int = 2, bf16: bool = True,
             d["b2"].append(_normal(r, (Hd,), 0.0, 0.02))
             d["ln2_g"].append(_normal(r, (Hd,), 1.0, 0.02))
             d["ln2_b"].append(_normal(r, (Hd,), 0.0, 0.02))
+            if rel:                                    # relative-position attention: drawn last, so the rest is unchanged
+                d.setdefault("Wr", []).append(_normal(r, (Hd, Hd), 0.0, 0.02))
+                d.setdefault("rwb", []).append(_normal(r, (Hd,), 0.0, 0.02))
+                d.setdefault("rrb", []).append(_normal(r, (Hd,), 0.0, 0.02))
     layers = []
     for d in per_layer:
         merged = {}
@@ -141,7 +156,10 @@ def encoder_stack(M: int, shape: EncoderShape, cfg: int = 2, bf16: bool = True,
             a = np.concatenate(lst) if k.startswith("ln") else np.stack(lst)
             merged[k] = _store(a, bf16)
         layers.append(merged)
-    return {"X": _store(np.stack(xs), bf16), "layers": layers}
+    out = {"X": _store(np.stack(xs), bf16), "layers": layers}
+    if rel:
+        out["R"] = _store(relative_positions(shape.seq, Hd), bf16)
+    return out
 
 
 # ----------------------------------------------------------------------------- workloads 3 and 4

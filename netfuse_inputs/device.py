@@ -35,7 +35,7 @@ def _fill(dst: torch.Tensor, g, mean, std):
 
 
 def encoder_stack_device(M: int, shape: EncoderShape, cfg: int = 5, dtype=torch.bfloat16,
-                         device="cuda") -> Dict[str, object]:
+                         device="cuda", rel: bool = False) -> Dict[str, object]:
     """X[M, batch*seq, hidden] ~ N(0,1); matrices ~ N(0,0.02) in ``dtype``; biases ~ N(0,0.02) and
     LayerNorm gamma ~ 1+N(0,0.02), beta ~ N(0,0.02) in float32 (values on the bf16 grid)."""
     Hd, F, N = shape.hidden, shape.ffn, shape.batch * shape.seq
@@ -56,10 +56,19 @@ def encoder_stack_device(M: int, shape: EncoderShape, cfg: int = 5, dtype=torch.
                 _fill(L[k][m], g, 0.0, 0.02)
             _fill(L["ln2_g"][m * Hd:(m + 1) * Hd], g, 1.0, 0.02)
             _fill(L["ln2_b"][m * Hd:(m + 1) * Hd], g, 0.0, 0.02)
+            if rel:
+                for k, shp in (("Wr", (M, Hd, Hd)), ("rwb", (M, Hd)), ("rrb", (M, Hd))):
+                    if k not in L:
+                        L[k] = e(*shp)
+                    _fill(L[k][m], g, 0.0, 0.02)
     for L in layers:                      # per-feature vectors are float32 operands (values on the storage grid)
-        for k in ("bqkv", "bo", "ln1_g", "ln1_b", "b1", "b2", "ln2_g", "ln2_b"):
+        for k in ("bqkv", "bo", "ln1_g", "ln1_b", "b1", "b2", "ln2_g", "ln2_b") + (("rwb", "rrb") if rel else ()):
             L[k] = L[k].to(torch.float32)
-    return {"X": X, "layers": layers}
+    out = {"X": X, "layers": layers}
+    if rel:
+        from . import relative_positions
+        out["R"] = torch.from_numpy(relative_positions(shape.seq, Hd)).to(device=device, dtype=dtype)
+    return out
 
 
 def resnet_params_device(spec: ResNetSpec, M: int, cfg: int = 3, dtype=torch.bfloat16,

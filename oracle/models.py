@@ -20,26 +20,32 @@ def tiny_layer(inp, M, out_bf16=False):
     return {"linear": Y, "layernorm": Z, "conv": C}
 
 
-def encoder_layer(X, Lw, M, batch, seq, heads, eps=1e-5, out_bf16=True, trace=None):
+def encoder_layer(X, Lw, M, batch, seq, heads, eps=1e-5, out_bf16=True, trace=None, R=None):
     """One post-LN encoder layer on X[M, batch*seq, hidden]:
     QKV = X Wqkv + b;  A = attention(QKV);  X1 = LN(A Wo + bo + X);
-    F = GELU(X1 W1 + b1) W2 + b2;  X2 = LN(F + X1)."""
+    F = GELU(X1 W1 + b1) W2 + b2;  X2 = LN(F + X1).
+    With R (the relative position encodings [2 seq, hidden]) the attention is the relative-position one:
+    Kr_m = R Wr_m, query biases rwb_m, rrb_m."""
     qkv = O.linear(X, Lw["Wqkv"], bias=Lw["bqkv"], out_bf16=out_bf16)
-    att = O.attention_packed(qkv, batch, seq, heads, out_bf16=out_bf16)
+    if R is None:
+        att = O.attention_packed(qkv, batch, seq, heads, out_bf16=out_bf16)
+    else:
+        kr = O.linear(np.broadcast_to(R, (M,) + R.shape).copy(), Lw["Wr"], out_bf16=out_bf16)
+        att = O.attention_relpos_packed(qkv, kr, batch, seq, heads, bias_w=Lw["rwb"], bias_r=Lw["rrb"], out_bf16=out_bf16)
     h = O.linear(att, Lw["Wo"], bias=Lw["bo"], residual=X, out_bf16=out_bf16)
     x1 = O.layernorm(h, Lw["ln1_g"], Lw["ln1_b"], M, eps=eps, out_bf16=out_bf16)
     f1 = O.linear(x1, Lw["W1"], bias=Lw["b1"], act=O.ACT_GELU, out_bf16=out_bf16)
     f2 = O.linear(f1, Lw["W2"], bias=Lw["b2"], residual=x1, out_bf16=out_bf16)
     x2 = O.layernorm(f2, Lw["ln2_g"], Lw["ln2_b"], M, eps=eps, out_bf16=out_bf16)
     if trace is not None:
-        trace.append(dict(qkv=qkv, att=att, h=h, x1=x1, f1=f1, f2=f2, x2=x2))
+        trace.append(dict(qkv=qkv, att=att, h=h, x1=x1, f1=f1, f2=f2, x2=x2) | ({} if R is None else {"kr": kr}))
     return x2
 
 
 def encoder_stack(inp, M, batch, seq, heads, eps=1e-5, out_bf16=True, trace=None):
     X = inp["X"]
     for Lw in inp["layers"]:
-        X = encoder_layer(X, Lw, M, batch, seq, heads, eps=eps, out_bf16=out_bf16, trace=trace)
+        X = encoder_layer(X, Lw, M, batch, seq, heads, eps=eps, out_bf16=out_bf16, trace=trace, R=inp.get("R"))
     return X
 
 

@@ -373,4 +373,282 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void a
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// bf16 MFMA kernel of the relative-position attention for head dimension 64: attention_mfma_d64_kernel with
+// the position term.  For a wave's 32 queries i0.. and a 32-key sub-block j0.. the positions S - i + j span
+// 63 consecutive rows of Kr starting at S - i0 + j0 - 31, so the term is computed as a dense 32 x 64 "band"
+// product RAW[o][i] = q_i . kr[base + o] on the matrix pipe (two more accumulators per sub-block) and the
+// diagonal bd[i][j] = RAW[(j - j0) - (i - i0) + 31][i] is picked out through a wave-private LDS tile (row =
+// query, pitch 66 floats: both the writes by position and the skewed reads by key are spread over the banks).
+// The query biases enter exactly, as two fp32 vectors per key block: c_j = bias_w . k_j per key and
+// e_p = bias_r . kr[p] per position, ((q + b) . k = q . k + b . k), one dot product per thread.
+// Workgroup = 128 queries of one (model, sequence, head); per key block of 64 keys it stages the 64 K and V
+// rows and the 192 Kr rows its four waves' bands cover (rows outside [0, 2S) are zero: they only meet
+// query/key pairs past the end).  One workgroup per CU (130 KB of LDS).
+// ------------------------------------------------------------------------------------------
+constexpr int kRelBand = 192;                              // Kr rows per (query block, key block)
+constexpr int kRelXPitch = 66;
+constexpr int kRelOffK = 0;
+constexpr int kRelOffV = kRelOffK + 2 * kAttnKB * kAttnKPitch * 2;
+constexpr int kRelOffR = kRelOffV + 2 * kAttnKB * kAttnVPitch * 2;
+constexpr int kRelOffX = kRelOffR + 2 * kRelBand * kAttnKPitch * 2;
+constexpr int kRelOffC = kRelOffX + 4 * 32 * kRelXPitch * 4;
+constexpr int kRelOffE = kRelOffC + kAttnKB * 4;
+constexpr int kRelLdsBytes = kRelOffE + kRelBand * 4;
+
+__global__ __launch_bounds__(256) void attention_relpos_mfma_d64_kernel(AttnRelArgs ra, int qblocks) {
+  const AttnArgs& a = ra.a;
+  extern __shared__ __align__(16) unsigned char rel_smem[];
+  lds_bf16_t* const Ks = (lds_bf16_t*)(rel_smem + kRelOffK);
+  lds_bf16_t* const Vs = (lds_bf16_t*)(rel_smem + kRelOffV);
+  lds_bf16_t* const Rs = (lds_bf16_t*)(rel_smem + kRelOffR);
+  lds_f32_t* const Xs = (lds_f32_t*)(rel_smem + kRelOffX);
+  lds_f32_t* const Cs = (lds_f32_t*)(rel_smem + kRelOffC);
+  lds_f32_t* const Es = (lds_f32_t*)(rel_smem + kRelOffE);
+  const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+  const int half = lane / 32, lq = lane % 32, l16 = lane % 16;
+  unsigned id = xcd_remap(blockIdx.x, gridDim.x);
+  const int qb = id % qblocks;  id /= qblocks;
+  const int h = id % a.heads;   id /= a.heads;
+  const int b = id % a.B;
+  const int m = id / a.B;
+  const long hd = (long)a.heads * kAttnD;
+  const long head_off = (long)m * a.stride_m + ((long)b * a.S) * a.stride_row + (long)h * kAttnD;
+  const bf16_t* Qp = (const bf16_t*)a.Q + head_off;
+  const bf16_t* Kp = (const bf16_t*)a.K + head_off;
+  const bf16_t* Vp = (const bf16_t*)a.V + head_off;
+  const bf16_t* Rp = (const bf16_t*)ra.Kr + (long)m * 2 * a.S * hd + (long)h * kAttnD;     // row p at + p * hd
+  const float* bw = ra.bias_w ? ra.bias_w + m * hd + h * kAttnD : nullptr;
+  const float* br = ra.bias_r ? ra.bias_r + m * hd + h * kAttnD : nullptr;
+  const float* mk = a.mask ? a.mask + ((long)m * a.B + b) * a.S : nullptr;
+  const float kLog2e = 1.4426950408889634f;
+  const float sc = a.scale * kLog2e;
+
+  const int q = qb * 128 + wave * 32 + lq;
+  bf16x8_t qf[kAttnD / 16];
+#pragma unroll
+  for (int kk = 0; kk < kAttnD / 16; ++kk) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (q < a.S) v = *reinterpret_cast<const uint4*>(Qp + (long)q * a.stride_row + kk * 16 + half * 8);
+    qf[kk] = __builtin_bit_cast(bf16x8_t, v);
+  }
+  f32x16_t o_acc[kAttnD / 32];
+#pragma unroll
+  for (int tb = 0; tb < kAttnD / 32; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o_acc[tb][r] = 0.f;
+  float mrun = -3.0e38f, lrun = 0.f;
+
+  // staging: 64 K rows, 64 V rows (2 chunks of 16 bytes per thread each) and 192 Kr rows (6 chunks per thread)
+  uint4 kreg[2], vreg[2], rreg[6];
+  auto fetch = [&](int j0) {
+    const int p0 = a.S - qb * 128 - 127 + j0;             // Kr row of band row 0
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int c = tid + t * 256, key = c / 8, kc = (c % 8) * 8;
+      kreg[t] = vreg[t] = make_uint4(0, 0, 0, 0);
+      if (j0 + key < a.S) {
+        kreg[t] = *reinterpret_cast<const uint4*>(Kp + (long)(j0 + key) * a.stride_row + kc);
+        vreg[t] = *reinterpret_cast<const uint4*>(Vp + (long)(j0 + key) * a.stride_row + kc);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 6; ++t) {
+      const int c = tid + t * 256, row = c / 8, kc = (c % 8) * 8;
+      const int p = p0 + row;
+      rreg[t] = make_uint4(0, 0, 0, 0);
+      if (p >= 0 && p < 2 * a.S) rreg[t] = *reinterpret_cast<const uint4*>(Rp + (long)p * hd + kc);
+    }
+  };
+  auto commit = [&](int stage) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int c = tid + t * 256, key = c / 8, kc = (c % 8) * 8;
+      lds_store16(Ks + stage * kAttnKB * kAttnKPitch + key * kAttnKPitch + kc, kreg[t]);
+      lds_store16(Vs + stage * kAttnKB * kAttnVPitch + key * kAttnVPitch + kc, vreg[t]);
+    }
+#pragma unroll
+    for (int t = 0; t < 6; ++t) {
+      const int c = tid + t * 256, row = c / 8, kc = (c % 8) * 8;
+      lds_store16(Rs + stage * kRelBand * kAttnKPitch + row * kAttnKPitch + kc, rreg[t]);
+    }
+  };
+  fetch(0);
+  commit(0);
+  __syncthreads();
+
+  lds_f32_t* const Xw = Xs + wave * 32 * kRelXPitch;       // this wave's exchange tile [query][position offset]
+  const int nblk = (a.S + kAttnKB - 1) / kAttnKB;
+  for (int blk = 0; blk < nblk; ++blk) {
+    const int j0 = blk * kAttnKB, cur = blk & 1;
+    if (blk + 1 < nblk) fetch(j0 + kAttnKB);
+    const lds_bf16_t* Kc = Ks + cur * kAttnKB * kAttnKPitch;
+    const lds_bf16_t* Vc = Vs + cur * kAttnKB * kAttnVPitch;
+    const lds_bf16_t* Rc = Rs + cur * kRelBand * kAttnKPitch;
+
+    // ---- the bias terms of this block: thread t < 64: c_t = bias_w . k_t; thread 64 + r: e_r = bias_r . kr[band row r]
+    {
+      const bool is_key = tid < kAttnKB;
+      const lds_bf16_t* row = is_key ? Kc + tid * kAttnKPitch : Rc + (tid - kAttnKB) * kAttnKPitch;
+      const float* bias = is_key ? bw : br;
+      float dot = 0.f;
+      if (bias != nullptr) {
+#pragma unroll
+        for (int c8 = 0; c8 < kAttnD / 8; ++c8) {
+          const u32x4_t v = *(const lds_u32x4_t*)(row + c8 * 8);
+          const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            dot = fmaf(bias[c8 * 8 + 2 * e], __uint_as_float(w[e] << 16), dot);
+            dot = fmaf(bias[c8 * 8 + 2 * e + 1], __uint_as_float(w[e] & 0xffff0000u), dot);
+          }
+        }
+      }
+      if (is_key) Cs[tid] = dot; else Es[tid - kAttnKB] = dot;
+    }
+    __syncthreads();
+
+    // ---- content scores, transposed (as attention_mfma_d64_kernel)
+    f32x16_t s_acc[2];
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_acc[sb][r] = 0.f;
+    {
+      bf16x8_t kf[kAttnD / 16][2];
+#pragma unroll
+      for (int kk = 0; kk < kAttnD / 16; ++kk)
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+          kf[kk][sb] = *(const lds_bf16x8_t*)(Kc + (sb * 32 + lq) * kAttnKPitch + kk * 16 + half * 8);
+#pragma unroll
+      for (int kk = 0; kk < kAttnD / 16; ++kk)
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+          s_acc[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk][sb], qf[kk], s_acc[sb], 0, 0, 0);
+    }
+    // ---- position term: band product, bias e, skew through the wave's LDS tile
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb) {
+      const int start = 96 - 32 * wave + 32 * sb;           // band row of position offset 0 for this wave and sub-block
+      f32x16_t rb[2];
+#pragma unroll
+      for (int ob = 0; ob < 2; ++ob)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) rb[ob][r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < kAttnD / 16; ++kk)
+#pragma unroll
+        for (int ob = 0; ob < 2; ++ob) {
+          const bf16x8_t rf = *(const lds_bf16x8_t*)(Rc + (start + ob * 32 + lq) * kAttnKPitch + kk * 16 + half * 8);
+          rb[ob] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf, qf[kk], rb[ob], 0, 0, 0);
+        }
+      // register r of block ob: position offset o = 32 ob + 8 (r/4) + 4 half + r%4, query lq
+#pragma unroll
+      for (int ob = 0; ob < 2; ++ob)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int o = 32 * ob + 8 * (r / 4) + 4 * half + (r % 4);
+          Xw[lq * kRelXPitch + o] = rb[ob][r] + Es[start + o];
+        }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int jj = 8 * (r / 4) + 4 * half + (r % 4);    // key within the sub-block
+        s_acc[sb][r] += Xw[lq * kRelXPitch + jj - lq + 31] + Cs[sb * 32 + jj];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();                      // the tile is rewritten for the next sub-block
+    }
+
+    if (mk != nullptr) {
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + sb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+          s_acc[sb][r] = fmaf(s_acc[sb][r], sc, (key < a.S ? mk[key] : 0.f) * kLog2e);
+        }
+    } else {
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_acc[sb][r] *= sc;
+    }
+    if (j0 + kAttnKB > a.S) {
+#pragma unroll
+      for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + sb * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+          s_acc[sb][r] = key < a.S ? s_acc[sb][r] : -3.0e38f;
+        }
+    }
+    float mloc = -3.0e38f;
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s_acc[sb][r]);
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, kWave));
+    const float mnew = fmaxf(mrun, mloc);
+    const float corr = __builtin_amdgcn_exp2f(mrun - mnew);
+    mrun = mnew;
+    float psum = 0.f;
+    bf16x8_t pf[2][2];
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int st = 0; st < 2; ++st) {
+        uint32_t w[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p0 = __builtin_amdgcn_exp2f(s_acc[sb][8 * st + 2 * e] - mnew);
+          const float p1 = __builtin_amdgcn_exp2f(s_acc[sb][8 * st + 2 * e + 1] - mnew);
+          w[e] = pack_bf16x2(p0, p1);
+          psum += p0 + p1;
+        }
+        uint4 v = make_uint4(w[0], w[1], w[2], w[3]);
+        pf[sb][st] = __builtin_bit_cast(bf16x8_t, v);
+      }
+    lrun = lrun * corr + psum;
+#pragma unroll
+    for (int tb = 0; tb < kAttnD / 32; ++tb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[tb][r] *= corr;
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int tb = 0; tb < kAttnD / 32; ++tb) {
+          const lds_bf16_t* vp = Vc + (sb * 32 + st * 16 + 4 * half + l16 / 4) * kAttnVPitch + tb * 32 +
+                                 ((lane / 16) % 2) * 16 + (l16 % 4) * 4;
+          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)vp);
+          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(vp + 8 * kAttnVPitch));
+          const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o_acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, both), pf[sb][st],
+                                                              o_acc[tb], 0, 0, 0);
+        }
+    if (blk + 1 < nblk) commit(cur ^ 1);
+    __syncthreads();
+  }
+
+  const float ltot = lrun + __shfl_xor(lrun, 32, kWave);
+  if (q < a.S) {
+    const float inv = 1.0f / ltot;
+    bf16_t* Op = (bf16_t*)a.O + (((long)m * a.B + b) * a.S + q) * hd + (long)h * kAttnD;
+#pragma unroll
+    for (int tb = 0; tb < kAttnD / 32; ++tb)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        uint2 v;
+        v.x = pack_bf16x2(o_acc[tb][4 * rg] * inv, o_acc[tb][4 * rg + 1] * inv);
+        v.y = pack_bf16x2(o_acc[tb][4 * rg + 2] * inv, o_acc[tb][4 * rg + 3] * inv);
+        *reinterpret_cast<uint2*>(Op + tb * 32 + 8 * rg + 4 * half) = v;
+      }
+  }
+}
+
 }  // namespace nf

@@ -8,6 +8,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 
 #include "../../include/netfuse.h"
 #include "attention_kernels.h"
@@ -717,6 +718,21 @@ nf_status netfuse_attention_relpos(const void* Q, const void* K, const void* V, 
   a.stride_m = stride_m; a.stride_row = stride_row; a.scale = scale;
   ra.Kr = Kr; ra.bias_w = bias_w; ra.bias_r = bias_r;
   hipStream_t s = (hipStream_t)stream;
+  if (dt == NF_BF16 && d == kAttnD && stride_row % 8 == 0 && stride_m % 8 == 0 && aligned(Q, 16) && aligned(K, 16) &&
+      aligned(V, 16) && aligned(Kr, 16) && aligned(O, 8) && S <= (1 << 24)) {
+    const int qblocks = (S + 127) / 128;
+    const long long total = prod({M, B, heads, qblocks});
+    if (total > kMaxGrid) return NF_EUNSUPPORTED;
+    static std::atomic<bool> opted_in{false};          // 130 KB of LDS: one opt-in per process (idempotent)
+    if (!opted_in.load(std::memory_order_acquire)) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(attention_relpos_mfma_d64_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kRelLdsBytes) != hipSuccess)
+        return NF_ELAUNCH;
+      opted_in.store(true, std::memory_order_release);
+    }
+    nf_launch(attention_relpos_mfma_d64_kernel, dim3((unsigned)total), dim3(256), kRelLdsBytes, s, ra, qblocks);
+    return launched();
+  }
   const int dpl = (d + 63) / 64;
 #define NF_ATTR(T, DPL) nf_launch((attention_relpos_kernel<T, DPL>), dim3((unsigned)blocks), dim3(256), 0, s, ra)
   if (dt == NF_F32) {

@@ -26,11 +26,15 @@ class EncoderStack:
     """Post-LN encoder layers on X[M, batch*seq, hidden] (workloads 2 and 5):
     QKV = X Wqkv + b; A = attention(QKV); X1 = LN(A Wo + bo + X); X2 = LN(GELU(X1 W1 + b1) W2 + b2 + X1)."""
 
-    MATS = ("Wqkv", "Wo", "W1", "W2")
+    MATS = ("Wqkv", "Wo", "W1", "W2", "Wr")
 
     def __init__(self, layers: List[Dict[str, torch.Tensor]], M: int, batch: int, seq: int, heads: int,
-                 eps: float = 1e-5, buffers: Optional[Dict[str, torch.Tensor]] = None):
+                 eps: float = 1e-5, buffers: Optional[Dict[str, torch.Tensor]] = None,
+                 R: Optional[torch.Tensor] = None):
+        """R[2*seq, hidden] (relative position encodings) switches the attention to the relative-position form
+        (XLNet-shaped layers): per layer Kr = R Wr (one more merged matmul) and the query biases rwb, rrb."""
         self.layers, self.M, self.batch, self.seq, self.heads, self.eps = layers, M, batch, seq, heads, eps
+        self.R = R
         W = layers[0]
         self.hidden, self.ffn = W["Wqkv"].shape[1], W["W1"].shape[2]
         N, Hd, F = batch * seq, self.hidden, self.ffn
@@ -39,6 +43,9 @@ class EncoderStack:
             e = lambda *s: torch.empty(s, dtype=dt, device=dev)
             buffers = dict(qkv=e(M, N, 3 * Hd), att=e(M, N, Hd), h=e(M, N, Hd), x1=e(M, N, Hd),
                            f1=e(M, N, F), f2=e(M, N, Hd), xa=e(M, N, Hd), xb=e(M, N, Hd))
+            if R is not None:
+                buffers["kr"] = e(M, 2 * seq, Hd)
+                buffers["Rrep"] = R.unsqueeze(0).expand(M, -1, -1).contiguous()      # the shared encodings, once per model
         self.buf = buffers
 
     @classmethod
@@ -46,19 +53,26 @@ class EncoderStack:
         layers = []
         for Lw in inp["layers"]:
             layers.append({k: to_device(v, dtype if k in cls.MATS else torch.float32) for k, v in Lw.items()})
-        return cls(layers, M, batch, seq, heads, eps)
+        R = to_device(inp["R"], dtype) if "R" in inp else None
+        return cls(layers, M, batch, seq, heads, eps, R=R)
 
     def layer(self, X, Lw, out, trace=None):
         b, M = self.buf, self.M
         nf.linear(X, Lw["Wqkv"], bias=Lw["bqkv"], out=b["qkv"])
-        nf.attention_packed(b["qkv"], self.batch, self.seq, self.heads, out=b["att"])
+        if self.R is None:
+            nf.attention_packed(b["qkv"], self.batch, self.seq, self.heads, out=b["att"])
+        else:
+            nf.linear(b["Rrep"], Lw["Wr"], out=b["kr"])
+            nf.attention_relpos_packed(b["qkv"], b["kr"], self.batch, self.seq, self.heads, bias_w=Lw["rwb"],
+                                       bias_r=Lw["rrb"], out=b["att"])
         nf.linear(b["att"], Lw["Wo"], bias=Lw["bo"], residual=X, out=b["h"])
         nf.layernorm(b["h"], Lw["ln1_g"], Lw["ln1_b"], M, eps=self.eps, out=b["x1"])
         nf.linear(b["x1"], Lw["W1"], bias=Lw["b1"], act=nf.ACT_GELU, out=b["f1"])
         nf.linear(b["f1"], Lw["W2"], bias=Lw["b2"], residual=b["x1"], out=b["f2"])
         nf.layernorm(b["f2"], Lw["ln2_g"], Lw["ln2_b"], M, eps=self.eps, out=out)
         if trace is not None:
-            trace.append({k: b[k].clone() for k in ("qkv", "att", "h", "x1", "f1", "f2")} | {"x2": out.clone()})
+            keys = ("qkv", "att", "h", "x1", "f1", "f2") + (("kr",) if self.R is not None else ())
+            trace.append({k: b[k].clone() for k in keys} | {"x2": out.clone()})
         return out
 
     def forward(self, X, trace=None):
@@ -78,7 +92,7 @@ class EncoderStack:
                     d[k] = v[m * Hd:(m + 1) * Hd] if k.startswith("ln") else v[m:m + 1]
                 layers.append(d)
             bufs = {k: v[m:m + 1] for k, v in self.buf.items()}
-            out.append(EncoderStack(layers, 1, self.batch, self.seq, self.heads, self.eps, bufs))
+            out.append(EncoderStack(layers, 1, self.batch, self.seq, self.heads, self.eps, bufs, R=self.R))
         return out
 
 

@@ -350,6 +350,9 @@ def test_attention(nf, oracle, dtype, M, B, S, heads, d, use_mask):
 
 
 @pytest.mark.parametrize("dtype,M,B,S,heads,d", [(torch.bfloat16, 2, 1, 48, 3, 64), (torch.bfloat16, 3, 2, 70, 2, 32),
+                                               (torch.bfloat16, 2, 1, 128, 2, 64),      # one full query block, two key blocks
+                                               (torch.bfloat16, 1, 2, 200, 1, 64),      # ragged second query block, four key blocks
+                                               (torch.bfloat16, 1, 1, 300, 1, 64),      # three query blocks: bands that start below row 0
                                                (torch.float32, 2, 1, 33, 2, 16), (torch.float32, 1, 1, 5, 1, 80)],
                          ids=lambda v: str(v).replace("torch.", ""))
 def test_attention_relpos(nf, oracle, dtype, M, B, S, heads, d):
@@ -362,6 +365,8 @@ def test_attention_relpos(nf, oracle, dtype, M, B, S, heads, d):
     ref = oracle.attention_relpos_packed(qkv, Kr, B, S, heads, bias_w=bw, bias_r=br, mask=mask, out_bf16=bf)
     got = nf.attention_relpos_packed(dev(qkv, dtype), dev(Kr, dtype), B, S, heads, bias_w=dev(bw), bias_r=dev(br), mask=dev(mask))
     check(host(got), ref, dtype, "relative-position attention")
+    nobias = nf.attention_relpos_packed(dev(qkv, dtype), dev(Kr, dtype), B, S, heads)
+    check(host(nobias), oracle.attention_relpos_packed(qkv, Kr, B, S, heads, out_bf16=bf), dtype, "no biases, no mask")
     plain = nf.attention_packed(dev(qkv, dtype), B, S, heads)
     zero = nf.attention_relpos_packed(dev(qkv, dtype), dev(np.zeros_like(Kr), dtype), B, S, heads)
     check(host(zero), host(plain), dtype, "zero position term")
@@ -643,6 +648,33 @@ def test_encoder_reduced_batch_per_model(nf, oracle, batch):
         _encoder_per_call_parity(oracle, trace[li], X_in, _slice_layer(enc.layers[li], list(range(M)), shape.hidden),
                                  list(range(M)), batch, shape.seq, shape.heads, torch.bfloat16)
     ref = OM.encoder_stack(inp, M, batch, shape.seq, shape.heads, out_bf16=True)
+    err = np.abs(host(out) - ref)
+    print("end-to-end max abs err %.4f mean %.5f" % (float(err.max()), float(err.mean())))
+    assert float(err.max()) < 0.15 and float(err.mean()) < 0.01
+    for m, one in enumerate(enc.per_model()):
+        assert torch.equal(one.forward(X[m:m + 1])[0], out[m])
+
+
+def test_encoder_with_relative_position_attention(nf, oracle):
+    """XLNet-shaped layers: the position projection as one more merged matmul, then the relative-position
+    attention; every call against the oracle, the chain end to end, merged == one model at a time."""
+    from oracle import models as OM
+    from paper_2009_13062_amd.workloads import EncoderStack
+    M = 3
+    shape = NI.EncoderShape(hidden=128, heads=2, ffn=256, layers=2, seq=40)
+    inp = NI.encoder_stack(M, shape, bf16=True, rel=True)
+    enc = EncoderStack.from_numpy(inp, M, 1, shape.seq, shape.heads)
+    X = dev(inp["X"], torch.bfloat16)
+    trace = []
+    out = enc.forward(X, trace)
+    bf = torch.bfloat16
+    for li, Lw in enumerate(inp["layers"]):
+        t = {k: host(v) for k, v in trace[li].items()}
+        Rrep = np.broadcast_to(inp["R"], (M,) + inp["R"].shape).copy()
+        check(t["kr"], oracle.linear(Rrep, Lw["Wr"], out_bf16=True), bf, "position projection")
+        check(t["att"], oracle.attention_relpos_packed(t["qkv"], t["kr"], 1, shape.seq, shape.heads, bias_w=Lw["rwb"],
+                                                       bias_r=Lw["rrb"], out_bf16=True), bf, "relative attention")
+    ref = OM.encoder_stack(inp, M, 1, shape.seq, shape.heads, out_bf16=True)
     err = np.abs(host(out) - ref)
     print("end-to-end max abs err %.4f mean %.5f" % (float(err.max()), float(err.mean())))
     assert float(err.max()) < 0.15 and float(err.mean()) < 0.01
