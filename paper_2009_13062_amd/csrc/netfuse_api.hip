@@ -624,6 +624,19 @@ nf_status netfuse_batchnorm(const void* x, const float* gamma, const float* beta
   const long long rowsbc = (long long)B * Ctot;
   if (rowsbc > kMaxGrid) return NF_EUNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
+  const long long n_el = prod({B, Ctot, HW});
+  const int per = 16 / (int)esz;
+  if (n_el % per == 0 && aligned(x, 16) && aligned(y, 16) && aligned(residual, 16) && n_el / per / 256 < kMaxGrid) {
+    const long long chunks = n_el / per;
+    const unsigned grid = (unsigned)((chunks + 255) / 256);
+    if (dt == NF_F32)
+      nf_launch(batchnorm_flat_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)x, gamma, beta, mean, var,
+                (const float*)residual, (float*)y, (int)Ctot, HW, eps, (int)act, (size_t)chunks);
+    else
+      nf_launch(batchnorm_flat_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, (const bf16_t*)x, gamma, beta, mean, var,
+                (const bf16_t*)residual, (bf16_t*)y, (int)Ctot, HW, eps, (int)act, (size_t)chunks);
+    return launched();
+  }
   const unsigned gy = (unsigned)((HW + 1023) / 1024 > 64 ? 64 : (HW + 1023) / 1024);
   if (dt == NF_F32)
     nf_launch(batchnorm_kernel<float>, dim3((unsigned)rowsbc, gy), dim3(256), 0, s, (const float*)x,

@@ -326,6 +326,25 @@ def test_batchnorm_fold_pools_transpose(nf, oracle, dtype):
     assert np.array_equal(host(nf.merge_transpose(t, 4, False)), src)
 
 
+@pytest.mark.parametrize("dtype", DTYPES, ids=ids)
+@pytest.mark.parametrize("M,C,B,H,W", [(2, 3, 1, 40, 40), (3, 5, 2, 7, 7), (2, 4, 1, 14, 14), (2, 3, 1, 1, 3), (2, 8, 1, 56, 56)],
+                         ids=["1600", "49", "196", "3-unaligned", "3136"])
+def test_batchnorm_plane_sizes(nf, oracle, M, C, B, H, W, dtype):
+    """Planes longer than a workgroup pass (HW > 1024), planes that end inside a 16-byte chunk (49, 196), a tensor
+    whose size is no multiple of the chunk (the per-plane kernel), with and without residual, in place."""
+    bf = dtype == torch.bfloat16
+    x, res = grid(rnd(B, M * C, H, W), dtype), grid(rnd(B, M * C, H, W), dtype)
+    g, b, mu = rnd(M * C, std=0.1, mean=1.0), rnd(M * C, std=0.1), rnd(M * C, std=0.1)
+    var = rng.uniform(0.5, 1.5, M * C).astype(np.float32)
+    for r in (None, res):
+        ref = oracle.batchnorm(x, g, b, mu, var, M, residual=r, act=1, out_bf16=bf)
+        got = nf.batchnorm(dev(x, dtype), dev(g), dev(b), dev(mu), dev(var), M, residual=None if r is None else dev(r, dtype), act=1)
+        check(host(got), ref, dtype, "batchnorm %s" % ((M, C, B, H, W),))
+    xd = dev(x, dtype)
+    nf.batchnorm(xd, dev(g), dev(b), dev(mu), dev(var), M, out=xd)
+    check(host(xd), oracle.batchnorm(x, g, b, mu, var, M, out_bf16=bf), dtype, "in place")
+
+
 # ------------------------------------------------------------------ attention
 @pytest.mark.parametrize("dtype,M,B,S,heads,d,use_mask", [
     (torch.bfloat16, 2, 1, 128, 12, 64, False),     # workload 2/5 shape
@@ -470,6 +489,40 @@ def test_merged_equals_m_separate_launches_bitwise(nf):
     for m, one in enumerate(enc.per_model()):
         out = one.forward(X[m:m + 1])
         assert torch.equal(out[0], merged[m])
+
+
+def test_graph_replay_equals_eager_forward(nf):
+    """What bench.py times is a captured HIP graph of the forward: its replays (several, with eager work and
+    synchronisations between them, on fresh inputs) give the eager result bit for bit."""
+    from paper_2009_13062_amd.workloads import EncoderStack, ResNetForward
+    M = 4
+    shape = NI.EncoderShape(hidden=256, heads=4, ffn=1024, layers=2, seq=128)
+    inp = NI.encoder_stack(M, shape, bf16=True)
+    enc = EncoderStack.from_numpy(inp, M, 1, shape.seq, shape.heads)
+    spec = NI.resnet_spec(cardinality=8, base_width=8, image=64, width_div=2, depths=(1, 1, 1, 1))
+    rinp = NI.resnet_params(spec, M, bf16=True)
+    net = ResNetForward.from_numpy(rinp, spec, M)
+    for fwd, x0 in ((enc.forward, dev(inp["X"], torch.bfloat16)), (net.forward, dev(rinp["x"], torch.bfloat16))):
+        x = x0.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fwd(x)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            out = fwd(x)
+        for rep in range(4):
+            x.copy_(x0 * (1.0 + 0.25 * rep))              # new input values in the captured buffer
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            replayed = out.clone()
+            eager = fwd(x).clone()                        # the program's own eager work between replays
+            torch.cuda.synchronize()
+            assert torch.equal(replayed, eager), "replay %d differs from the eager forward" % rep
+            assert torch.isfinite(eager.float()).all()
 
 
 def test_runs_are_bit_reproducible(nf):
