@@ -54,9 +54,9 @@ static nf_status launch_stream(GemmLaunch& L, int nsub, hipStream_t s) {
     // the tiles of a workgroup lie in one panel, or every tile is a panel
     if (a.panel != Cfg::kBN && a.panel % (nsub * Cfg::kBN)) return NF_EUNSUPPORTED;
   }
-  // the register epilogue moves 8 bytes per lane and reads the column constants 16 bytes at a time
-  if (a.ldc % 4 || ((uintptr_t)a.C & 7) || ((uintptr_t)a.R & 7) || ((uintptr_t)a.ep.col_bias & 15) ||
-      a.ep.col_vec_stride0 % 4 || a.ep.col_vec_stride1 % 4 || a.sC0 % 4 || a.sC1 % 4)
+  // the register epilogue moves 16 bytes per lane (output, residual, column constants)
+  if (a.ldc % 8 || ((uintptr_t)a.C & 15) || ((uintptr_t)a.R & 15) || ((uintptr_t)a.ep.col_bias & 15) ||
+      a.ep.col_vec_stride0 % 4 || a.ep.col_vec_stride1 % 4 || a.sC0 % 8 || a.sC1 % 8)
     return NF_EUNSUPPORTED;
   if (!a.ep.act_before_residual && a.ep.act != NF_ACT_NONE && a.R) return NF_EUNSUPPORTED;
   if (a.ep.row_bias || a.ep.row_scale) return NF_EUNSUPPORTED;

@@ -8,10 +8,9 @@
 // 60-80 VALU clocks per element with nothing else in flight, and the staging of the accumulators through
 // LDS adds four workgroup barriers -- while the same operand stream without any epilogue runs at the rate of
 // a plain read kernel (6 TB/s).  Here
-//   * the epilogue touches no LDS and no barrier: a lane owns 4 consecutive columns of a row (the
-//     accumulators are computed transposed), so it loads 8 bytes of residual, converts and stores 8 bytes;
-//     32 lanes x 2 halves write 32 rows x 16 bytes per instruction and four such instructions complete
-//     64 contiguous bytes per row, which the L2 merges before they reach HBM;
+//   * the epilogue touches no LDS and no barrier: a lane owns groups of 4 consecutive columns of a row (the
+//     accumulators are computed transposed); the two lanes of a row swap half of their groups so that each
+//     holds 8 consecutive columns, loads 16 bytes of residual, converts and stores 16 bytes;
 //   * the load pipeline never drains between the tiles of a workgroup: the stage counter runs over
 //     NSUB x K/BK steps, the source pointers jump to the next tile after a tile's last k-step, so
 //     NS-1 stages of the NEXT tile are in flight during an epilogue, and every wave starts the next tile
@@ -23,8 +22,12 @@
 
 namespace nf {
 
-// Epilogue of one whole BM x BN tile straight from the accumulators (layout: see gemm_mfma.h).
-// Needs 8-byte aligned rows of C and R (ldc % 4 == 0) and a 16-byte aligned column-constant vector.
+// Epilogue of one whole BM x BN tile straight from the accumulators (layout: see gemm_mfma.h): a lane holds,
+// per 32 x 32 block, four groups of 4 consecutive columns of its row (columns 8 q + 4 half + 0..3).  The two
+// lanes of a row (lane and lane + 32) swap one group per pair of groups, after the activation, so that each
+// ends up with 8 consecutive columns: residual and output then move 16 bytes per lane (8-byte stores
+// measured 1.4x the algorithmic write traffic: partially written sectors reaching HBM).
+// Needs 16-byte aligned rows of C and R (ldc % 8 == 0) and a 16-byte aligned column-constant vector.
 template <class Cfg, int ACT>
 __device__ __forceinline__ void stream_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::FN], bf16_t* C, const bf16_t* R,
                                                     long ldc, const float* col_bias) {
@@ -34,28 +37,49 @@ __device__ __forceinline__ void stream_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg
   const int half = lane / 32, l32 = lane % 32;
 #pragma unroll
   for (int j = 0; j < FN; ++j) {
-    const int col0 = wn * Cfg::WN + j * 32 + half * 4;
+    const int colb = wn * Cfg::WN + j * 32;
     float4 cb[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      cb[q] = col_bias ? *reinterpret_cast<const float4*>(col_bias + col0 + q * 8) : make_float4(0.f, 0.f, 0.f, 0.f);
+      cb[q] = col_bias ? *reinterpret_cast<const float4*>(col_bias + colb + q * 8 + half * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-      const long off = (long)(wm * Cfg::WM + i * 32 + l32) * ldc + col0;
-      uint2 rr[4];
+      // this lane's two 8-column pieces: columns colb + 16 qq + 8 half + 0..7
+      const long off = (long)(wm * Cfg::WM + i * 32 + l32) * ldc + colb + half * 8;
+      uint4 rr[2];
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        rr[q] = R ? *reinterpret_cast<const uint2*>(R + off + q * 8) : make_uint2(0u, 0u);
+      for (int qq = 0; qq < 2; ++qq)
+        rr[qq] = R ? *reinterpret_cast<const uint4*>(R + off + qq * 16) : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float b[4] = {cb[q].x, cb[q].y, cb[q].z, cb[q].w};
-        const uint32_t w[2] = {rr[q].x, rr[q].y};
-        float v[4];
+      for (int qq = 0; qq < 2; ++qq) {
+        float own[4], send[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = act_const<ACT>(fmaf(acc[i][j][q * 4 + e] + b[e] + 0.f, 1.f, 0.f));
-        const float o0 = v[0] + __uint_as_float(w[0] << 16), o1 = v[1] + __uint_as_float(w[0] & 0xffff0000u);
-        const float o2 = v[2] + __uint_as_float(w[1] << 16), o3 = v[3] + __uint_as_float(w[1] & 0xffff0000u);
-        *reinterpret_cast<uint2*>(C + off + q * 8) = make_uint2(pack_bf16x2(o0, o1), pack_bf16x2(o2, o3));
+        for (int e = 0; e < 4; ++e) {
+          // group 2 qq + half stays (its other half comes from the partner), group 2 qq + 1 - half is sent
+          const float b0[4] = {cb[2 * qq].x, cb[2 * qq].y, cb[2 * qq].z, cb[2 * qq].w};
+          const float b1[4] = {cb[2 * qq + 1].x, cb[2 * qq + 1].y, cb[2 * qq + 1].z, cb[2 * qq + 1].w};
+          const float v0 = act_const<ACT>(fmaf(acc[i][j][(2 * qq) * 4 + e] + b0[e] + 0.f, 1.f, 0.f));
+          const float v1 = act_const<ACT>(fmaf(acc[i][j][(2 * qq + 1) * 4 + e] + b1[e] + 0.f, 1.f, 0.f));
+          own[e] = half ? v1 : v0;
+          send[e] = half ? v0 : v1;
+        }
+        float recv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) recv[e] = __shfl_xor(send[e], 32, kWave);
+        // columns within the piece: the lower lane's group sits at 4 half' ... : half 0 holds columns 0..3 of its
+        // group and receives 4..7; half 1 holds 4..7 and receives 0..3
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          v[e] = half ? recv[e] : own[e];
+          v[4 + e] = half ? own[e] : recv[e];
+        }
+        const uint32_t w[4] = {rr[qq].x, rr[qq].y, rr[qq].z, rr[qq].w};
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          o[e] = pack_bf16x2(v[2 * e] + __uint_as_float(w[e] << 16), v[2 * e + 1] + __uint_as_float(w[e] & 0xffff0000u));
+        *reinterpret_cast<uint4*>(C + off + qq * 16) = make_uint4(o[0], o[1], o[2], o[3]);
       }
     }
   }
