@@ -117,7 +117,7 @@ class OpTimer:
             # per model: activations in, weights, activations out (2 bytes each)
             return "linear_%dx%dx%d" % (N, K, No), 2.0 * M * N * K * No, X.element_size() * (X.numel() + W.numel() + y_.numel())
 
-        def d_linear_packed(y_, X, Wp, panel, **kw):
+        def d_linear_packed(y_, X, Wp, **kw):
             return d_linear(y_, X, Wp, **kw)
 
         def d_conv(y_, x, w, M, g=1, bias=None, scale=None, shift=None, residual=None, stride=1, pad=0, **kw):
@@ -207,6 +207,9 @@ def roofline_for(agg):
 
 
 # ------------------------------------------------------------------------------------------
+PACKED_WEIGHTS = True     # encoder matmuls on weights packed once by netfuse_linear_pack_weight (--unpacked: off)
+
+
 def build_workload(name, torch, M=None, batch=1):
     """-> (forward(), [per-model forward()], config, M, inferences per step)."""
     import netfuse_inputs as NI
@@ -221,10 +224,11 @@ def build_workload(name, torch, M=None, batch=1):
         for r in range(rot):
             inp = encoder_stack_device(M, shape, cfg=p["cfg"] + 100 * r, rel=p.get("rel", False))
             nets.append(EncoderStack(inp["layers"], M, batch, shape.seq, shape.heads,
-                                     buffers=nets[0].buf if nets else None, R=inp.get("R")))
+                                     buffers=nets[0].buf if nets else None, R=inp.get("R"), packed=PACKED_WEIGHTS))
             x = inp["X"] if x is None else x
         cfg = dict(workload=name, M=M, layers=shape.layers, seq_len=shape.seq, hidden=shape.hidden,
-                   heads=shape.heads, ffn=shape.ffn, batch_per_model=batch, weight_copies_rotated=rot)
+                   heads=shape.heads, ffn=shape.ffn, batch_per_model=batch, weight_copies_rotated=rot,
+                   packed_weights=PACKED_WEIGHTS)
 
         def merged():
             for n in nets:
@@ -485,6 +489,7 @@ def main():
     ap.add_argument("--others", default="encoder12_m32_s512,xlnet12_m32_s128,resnet50_m32,resnext50_32x4d_m16,encoder1_m8_s128",
                     help="comma list of further workloads reported under 'other_workloads' ('' = none)")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--unpacked", action="store_true", help="encoder matmuls on the row-major weights (netfuse_linear) instead of the packed ones")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweeps", action="store_true", help="skip the model-count and batch-size sweeps")
     ap.add_argument("--quick", action="store_true", help="headline workload only: no sweeps, no other workloads, no CPU baseline")
@@ -501,6 +506,8 @@ def main():
     import paper_2009_13062_amd as nf
     torch.cuda.set_device(0)
     events = HipEvents()
+    global PACKED_WEIGHTS
+    PACKED_WEIGHTS = not args.unpacked
 
     if args.calibrate_copy:
         calibrate_copy(torch, nf)

@@ -63,24 +63,26 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
  * the M weight matrices are concatenated once when the models are merged; at inference they are
  * static and are nearly all of the bytes a forward pass reads).
  *
- * Packed layout, for a panel width `panel` (a multiple of 32 that divides Nout; K a multiple of 32):
- *   Wp[m][p][kb][j][r][c] = W[m][32 kb + r][panel p + 32 j + c]      0 <= r, c < 32,
- *   p < Nout/panel, kb < K/32, j < panel/32  -- i.e. 2 KB blocks of 32 k x 32 n, the blocks of one
- *   k-block of a panel contiguous, then the next k-block, then the next panel, then the next model.
- *   Same element count as W.  bf16 only (NF_EUNSUPPORTED for float).
- * netfuse_linear_packed_panel: the panel width the kernel chosen for (M, N, K, Nout) streams as one
- *   contiguous run per workgroup, or 0 if this shape has no packed kernel (then use
- *   netfuse_linear).  Any multiple of it that divides Nout is accepted by the other two calls.
- * netfuse_linear_pack_weight: W[M][K][Nout] -> Wp; W and Wp must not overlap; 16-byte aligned.
- * netfuse_linear_packed: Y[m] = act(X[m] . W[m] + bias[m]) + residual[m] as netfuse_linear, bit for
- *   bit the same result; NF_EUNSUPPORTED if N, K, Nout are not whole tiles of a packed kernel.
+ * Packed layout (K a multiple of 16, Nout a multiple of 32; same element count as W; bf16 only,
+ * NF_EUNSUPPORTED for float): the operand fragments of the 32x32x16 matrix instruction,
+ *   Wp[m][j][s][l][e] = W[m][16 s + 8 (l / 32) + e][32 j + l % 32]
+ *   j < Nout/32 (column block), s < K/16 (k slice), l < 64 (lane), e < 8,
+ * so the 1 KB a wavefront loads for one multiplication is contiguous, the slices of a column block
+ * follow one another down k, then the next column block, then the next model.
+ * netfuse_linear_packed_supported: 1 if netfuse_linear_packed has a kernel for (M, N, K, Nout)
+ *   (N a multiple of 128; Nout a multiple of 96 with K % 256 == 0, or of 288 or 384 with K % 128 == 0),
+ *   else 0 (then use netfuse_linear).
+ * netfuse_linear_pack_weight: W[M][K][Nout] -> Wp; W and Wp must not overlap; Wp 16-byte aligned.
+ * netfuse_linear_packed: Y[m] = act(X[m] . W[m] + bias[m]) + residual[m] as netfuse_linear (the
+ *   products are summed in fp32 in a different order, so results can differ from it in the last bit);
+ *   X, residual, Y, bias 16-byte aligned; NF_EUNSUPPORTED where ..._supported returns 0.
  */
-int netfuse_linear_packed_panel(int M, int N, int K, int Nout, nf_dtype dt);
-nf_status netfuse_linear_pack_weight(const void* W, void* Wp, int M, int K, int Nout, int panel,
-                                     nf_dtype dt, void* stream);
+int netfuse_linear_packed_supported(int M, int N, int K, int Nout, nf_dtype dt);
+nf_status netfuse_linear_pack_weight(const void* W, void* Wp, int M, int K, int Nout, nf_dtype dt,
+                                     void* stream);
 nf_status netfuse_linear_packed(const void* X, const void* Wp, const float* bias, const void* residual,
-                                void* Y, int M, int N, int K, int Nout, int panel, nf_dtype dt,
-                                nf_act act, void* stream);
+                                void* Y, int M, int N, int K, int Nout, nf_dtype dt, nf_act act,
+                                void* stream);
 
 /*
  * Ragged merged matmul: the per-task output layers of fine-tuned models have a different number of

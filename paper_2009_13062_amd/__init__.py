@@ -27,7 +27,7 @@ MERGE_BATCH, MERGE_CHANNEL = 0, 1
 EXPORTS = ("netfuse_linear", "netfuse_conv2d", "netfuse_layernorm", "netfuse_batchnorm",
            "netfuse_bn_fold", "netfuse_attention", "netfuse_maxpool2d", "netfuse_avgpool_global",
            "netfuse_merge_transpose", "netfuse_linear_pack_weight", "netfuse_linear_packed",
-           "netfuse_time_next_launch", "netfuse_linear_packed_panel", "netfuse_linear_ragged",
+           "netfuse_time_next_launch", "netfuse_linear_packed_supported", "netfuse_linear_ragged",
            "netfuse_attention_relpos", "netfuse_strerror")
 
 
@@ -53,9 +53,9 @@ def _load() -> ctypes.CDLL:
     lib.netfuse_maxpool2d.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp]
     lib.netfuse_avgpool_global.argtypes = [vp, vp, i, i, i, i, vp]
     lib.netfuse_merge_transpose.argtypes = [vp, vp, i, i, i, i, i, vp]
-    lib.netfuse_linear_packed_panel.argtypes = [i, i, i, i, i]
-    lib.netfuse_linear_pack_weight.argtypes = [vp, vp, i, i, i, i, i, vp]
-    lib.netfuse_linear_packed.argtypes = [vp, vp, fp, vp, vp, i, i, i, i, i, i, i, vp]
+    lib.netfuse_linear_packed_supported.argtypes = [i, i, i, i, i]
+    lib.netfuse_linear_pack_weight.argtypes = [vp, vp, i, i, i, i, vp]
+    lib.netfuse_linear_packed.argtypes = [vp, vp, fp, vp, vp, i, i, i, i, i, i, vp]
     lib.netfuse_time_next_launch.argtypes = [vp, vp]
     lib.netfuse_attention_relpos.argtypes = [vp, vp, vp, vp, fp, fp, fp, vp, i, i, i, i, i, l, l, f, i, vp]
     lib.netfuse_linear_ragged.argtypes = [vp, vp, fp, vp, i, i, i, ctypes.POINTER(ctypes.c_int), i, i, vp]
@@ -116,22 +116,22 @@ def linear(X, W, bias=None, residual=None, act=ACT_NONE, out=None, stream=None):
     return Y
 
 
-def linear_packed_panel(M, N, K, Nout, dtype=torch.bfloat16) -> int:
-    """Panel width to pack W[M,K,Nout] with for N rows per model; 0 = no packed kernel for this shape."""
-    return int(lib.netfuse_linear_packed_panel(M, N, K, Nout, NF_BF16 if dtype == torch.bfloat16 else NF_F32))
+def linear_packed_supported(M, N, K, Nout, dtype=torch.bfloat16) -> bool:
+    """True if linear_packed has a kernel for N rows per model of W[M,K,Nout]."""
+    return bool(lib.netfuse_linear_packed_supported(M, N, K, Nout, NF_BF16 if dtype == torch.bfloat16 else NF_F32))
 
 
-def linear_pack_weight(W, panel, out=None, stream=None):
-    """W[M,K,Nout] -> block-packed copy (same shape and dtype, layout of include/netfuse.h)."""
+def linear_pack_weight(W, out=None, stream=None):
+    """W[M,K,Nout] -> fragment-packed copy (same shape and dtype, layout of include/netfuse.h)."""
     M, K, Nout = W.shape
     Wp = torch.empty_like(W) if out is None else out
     _check("netfuse_linear_pack_weight", lib.netfuse_linear_pack_weight(
-        _ptr(W), _ptr(Wp, W), M, K, Nout, int(panel), _dt(W), _stream(stream)))
+        _ptr(W), _ptr(Wp, W), M, K, Nout, _dt(W), _stream(stream)))
     return Wp
 
 
-def linear_packed(X, Wp, panel, bias=None, residual=None, act=ACT_NONE, out=None, stream=None):
-    """netfuse_linear on weights packed by linear_pack_weight(W, panel); Wp keeps W's shape [M,K,Nout]."""
+def linear_packed(X, Wp, bias=None, residual=None, act=ACT_NONE, out=None, stream=None):
+    """netfuse_linear on weights packed by linear_pack_weight(W); Wp keeps W's shape [M,K,Nout]."""
     M, N, K = X.shape
     Nout = Wp.shape[2]
     if Wp.shape[0] != M or Wp.shape[1] != K:
@@ -139,7 +139,7 @@ def linear_packed(X, Wp, panel, bias=None, residual=None, act=ACT_NONE, out=None
     Y = torch.empty((M, N, Nout), dtype=X.dtype, device=X.device) if out is None else out
     _check("netfuse_linear_packed", lib.netfuse_linear_packed(
         _ptr(X), _ptr(Wp, X), _ptr(bias, f32=True), _ptr(residual, X), _ptr(Y, X), M, N, K, Nout,
-        int(panel), _dt(X), int(act), _stream(stream)))
+        _dt(X), int(act), _stream(stream)))
     return Y
 
 

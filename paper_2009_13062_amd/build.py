@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnetfuse.so")
 SOURCES = ["netfuse_api.hip", "graph_merge.cpp", "gemm_inst_b8.hip", "gemm_inst_b2.hip", "gemm_inst_b24.hip", "gemm_inst_b22.hip", "gemm_inst_b21.hip", "gemm_inst_b27.hip", "gemm_inst_b1.hip",
-           "gemm_inst_b0.hip", "gemm_inst_dma.hip", "gemm_inst_stream.hip", "conv_patch_inst.hip", "conv_tap_inst.hip"]
+           "gemm_inst_b0.hip", "gemm_inst_dma.hip", "gemm_inst_stream.hip", "gemm_inst_frag.hip", "conv_patch_inst.hip", "conv_tap_inst.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -124,12 +124,7 @@ __device__ __forceinline__ void touch_a_rows(const bf16_t* A, long lda, int K, i
 #endif
 }
 
-// PACKED: B points at this tile's first block of a block-packed weight tensor (netfuse_linear_pack_weight):
-// 2 KB blocks of [32 k][32 n], the BN/32 blocks of one k-block contiguous, consecutive k-blocks `ldb`
-// ELEMENTS apart.  A stage's B region then is [BK/32][BN/32] such blocks, each copied as two contiguous 1 KB
-// wave loads; the 64-byte row pitch inside a block needs no bank permutation for the transposing read (the
-// four k rows x two 16-column halves touched by 32 lanes tile 256 bytes exactly).
-template <class Cfg, bool PACKED = false>
+template <class Cfg>
 __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long lda, const bf16_t* __restrict__ B,
                                               long ldb, int K, lds_u8_t* smem, bf16_t* C, const bf16_t* R,
                                               long ldc, const Epilogue& ep, long row_vec_off, long col_vec_off,
@@ -151,11 +146,6 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
       const int c = (lane % Cfg::kACpr) ^ Cfg::swz_a(row);
       src[t] = A + (long)row * lda + c * 8;
       inc[t] = BK;
-    } else if constexpr (PACKED) {
-      constexpr int kHalves = Cfg::kBN / 16;                 // 1 KB halves per k-block of the tile
-      const int hb = blk - Cfg::kABlocks;
-      src[t] = B + (long)(hb / kHalves) * ldb + (hb % kHalves) * 512 + lane * 8;
-      inc[t] = (long)(BK / 32) * ldb;
     } else {
       const int flat = (blk - Cfg::kABlocks) * 64 + lane;    // chunk index in the row-major [BK][BN] LDS tile
       const int krow = flat / Cfg::kBCpr;
@@ -197,14 +187,11 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
     for (int hl = 0; hl < 2; ++hl) {
       const int kr = 8 * half + l16 / 4 + 4 * hl;     // row inside a 16-k step; kr % 4 = l16 / 4
       const int n = wn * Cfg::WN + j * 32 + ((lane / 16) % 2) * 16 + (l16 % 4) * 4;
-      if constexpr (PACKED)
-        b_off[j][hl] = Cfg::kABytes + (n / 32) * 2048 + kr * 64 + (n % 32) * 2;
-      else
-        b_off[j][hl] = Cfg::kABytes + kr * Cfg::kBRow + (((n / 8) ^ (Cfg::kBSwz * (l16 / 4))) * 16) + ((n / 4) % 2) * 8;
+      b_off[j][hl] = Cfg::kABytes + kr * Cfg::kBRow + (((n / 8) ^ (Cfg::kBSwz * (l16 / 4))) * 16) + ((n / 4) % 2) * 8;
     }
   // byte offset of the kk-th 16-k step of a stage's B region
   auto b_step = [](int kk) {
-    return PACKED ? (kk / 2) * (Cfg::kBN / 32) * 2048 + (kk % 2) * 16 * 64 : kk * 16 * Cfg::kBRow;
+    return kk * 16 * Cfg::kBRow;
   };
 
   f32x16_t acc[FM][FN];
@@ -243,18 +230,20 @@ __device__ __forceinline__ void gemm_dma_tile(const bf16_t* __restrict__ A, long
         bfr[kk][j] = __builtin_bit_cast(bf16x8_t, both);
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
-    wait_lgkmcnt0();
-    __builtin_amdgcn_sched_barrier(0);
-    if (kt + NS - 1 < nk) issue_stage(kt + NS - 1);   // refills the stage read in step kt-1
+    // The multiplications start as soon as the fragments of the first 16-k slice are there; the next stage's
+    // loads are issued behind the last slice (they refill the stage read in step kt-1).
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk)
+    for (int kk = 0; kk < BK / 16; ++kk) {
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (kt + NS - 1 < nk) issue_stage(kt + NS - 1);
+    __builtin_amdgcn_sched_barrier(0);
   }
   __syncthreads();   // every wave is done with the last stage before the epilogue reuses LDS
   gemm_epilogue<Cfg>(acc, (lds_f32_t*)smem, C, R, ldc, Cfg::kBM, Cfg::kBN, ep, row_vec_off, col_vec_off);

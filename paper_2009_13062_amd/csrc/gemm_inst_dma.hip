@@ -36,30 +36,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_dma_kernel(GemmArgs a) {
                      tn, a.touch_a ? a.tiles_n : 0);
 }
 
-// B is block-packed: [problem][panel][K/32][panel/32] blocks of [32 k][32 n] (see netfuse_linear_pack_weight)
 template <class Cfg>
-__global__ __launch_bounds__(Cfg::kThreads) void gemm_dma_packed_kernel(GemmArgs a) {
-  extern __shared__ __align__(1024) unsigned char smem_raw[];
-  lds_u8_t* smem = (lds_u8_t*)smem_raw;
-  unsigned id = xcd_remap(blockIdx.x, gridDim.x);
-  const int tm = id % a.tiles_m;  id /= a.tiles_m;
-  const int tn = id % a.tiles_n;  id /= a.tiles_n;
-  const int z0 = id % a.nz0;
-  const int z1 = id / a.nz0;
-  const int row0 = tm * Cfg::kBM, col0 = tn * Cfg::kBN;
-  const long coff = z0 * a.sC0 + z1 * a.sC1 + (long)row0 * a.ldc + col0;
-  const bf16_t* A = a.A + z0 * a.sA0 + z1 * a.sA1 + (long)row0 * a.lda;
-  const int pb = a.panel / 32;                                  // blocks per k-block of a panel
-  const long kb_stride = (long)pb * 1024;                       // elements between consecutive k-blocks
-  const bf16_t* B = a.B + z0 * a.sB0 + z1 * a.sB1 + (long)(col0 / a.panel) * (a.K / 32) * kb_stride +
-                    (long)((col0 % a.panel) / 32) * 1024;
-  const long rvo = z0 * a.ep.row_vec_stride0 + z1 * a.ep.row_vec_stride1 + row0;
-  const long cvo = z0 * a.ep.col_vec_stride0 + z1 * a.ep.col_vec_stride1 + col0;
-  gemm_dma_tile<Cfg, true>(A, a.lda, B, kb_stride, a.K, smem, a.C + coff, a.R ? a.R + coff : nullptr, a.ldc, a.ep,
-                           rvo, cvo, tn, a.touch_a ? a.tiles_n : 0);
-}
-
-template <class Cfg, bool PACKED = false>
 nf_status launch_dma(GemmLaunch& L, hipStream_t s) {
   GemmArgs& a = L.a;
   if (a.rows % Cfg::kBM || a.cols % Cfg::kBN || a.K % Cfg::kBK) return NF_EUNSUPPORTED;
@@ -68,9 +45,7 @@ nf_status launch_dma(GemmLaunch& L, hipStream_t s) {
   const long long total = (long long)a.tiles_m * a.tiles_n * a.nz0 * L.nz1;
   if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
   a.touch_a = touch_a_pays(total, (long long)a.rows * a.K, (long long)a.nz0 * L.nz1);
-  if (PACKED && (a.panel <= 0 || a.panel % Cfg::kBN || a.cols % a.panel || a.K % 32)) return NF_EUNSUPPORTED;
-  void (*kern)(GemmArgs);
-  if constexpr (PACKED) kern = gemm_dma_packed_kernel<Cfg>; else kern = gemm_dma_kernel<Cfg>;
+  auto kern = gemm_dma_kernel<Cfg>;
   if (Cfg::kLdsBytes > 64 * 1024) {
     static std::atomic<bool> opted_in{false};
     if (!opted_in.load(std::memory_order_acquire)) {
@@ -82,18 +57,6 @@ nf_status launch_dma(GemmLaunch& L, hipStream_t s) {
   }
   nf_launch(kern, dim3((unsigned)total), dim3(Cfg::kThreads), Cfg::kLdsBytes, s, a);
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
-}
-
-nf_status launch_gemm_dma_packed(int cfg, GemmLaunch& L, hipStream_t s) {
-  switch (cfg) {
-    case D256x256k32s4: return launch_dma<DmaCfg<256, 256, 32, 2, 4, 4>, true>(L, s);
-    case D128x128k32s4: return launch_dma<DmaCfg<128, 128, 32, 2, 4, 4>, true>(L, s);
-    case D128x128k64s3w8: return launch_dma<DmaCfg<128, 128, 64, 2, 4, 3>, true>(L, s);
-    case D128x384k32s4w12: return launch_dma<DmaCfg<128, 384, 32, 2, 6, NF_NS_384>, true>(L, s);
-    case D128x288k32s4w12: return launch_dma<DmaCfg<128, 288, 32, 4, 3, NF_NS_288>, true>(L, s);
-    case D128x96k64s4w12: return launch_dma<DmaCfg<128, 96, 64, 4, 3, NF_NS_96>, true>(L, s);
-  }
-  return NF_EUNSUPPORTED;
 }
 
 nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s) {

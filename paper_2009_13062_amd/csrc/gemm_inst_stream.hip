@@ -10,7 +10,7 @@
 
 namespace nf {
 
-template <class Cfg, bool PACKED>
+template <class Cfg>
 __global__ __launch_bounds__(Cfg::kThreads) void gemm_stream_kernel(GemmArgs a, int nsub) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   lds_u8_t* smem = (lds_u8_t*)smem_raw;
@@ -25,35 +25,18 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_stream_kernel(GemmArgs a, 
   const long coff = z0 * a.sC0 + z1 * a.sC1 + (long)row0 * a.ldc + col0;
   const bf16_t* A = a.A + z0 * a.sA0 + z1 * a.sA1 + (long)row0 * a.lda;
   const float* bias = a.ep.col_bias ? a.ep.col_bias + z0 * a.ep.col_vec_stride0 + z1 * a.ep.col_vec_stride1 + col0 : nullptr;
-  const bf16_t* B;
-  long ldb, tile_stride;
-  if constexpr (PACKED) {
-    const int pb = a.panel / 32;
-    ldb = (long)pb * 1024;                                      // elements between consecutive k-blocks
-    B = a.B + z0 * a.sB0 + z1 * a.sB1 + (long)(col0 / a.panel) * (a.K / 32) * ldb + (long)((col0 % a.panel) / 32) * 1024;
-    // consecutive tiles: side by side inside a panel, or (panel == tile width) one whole panel apart
-    tile_stride = a.panel == Cfg::kBN ? (long)(a.K / 32) * ldb : (long)(Cfg::kBN / 32) * 1024;
-  } else {
-    ldb = a.ldb;
-    B = a.B + z0 * a.sB0 + z1 * a.sB1 + col0;
-    tile_stride = Cfg::kBN;
-  }
-  gemm_stream_tiles<Cfg, PACKED>(A, a.lda, B, ldb, tile_stride, a.K, nsub, smem, a.C + coff,
+  const bf16_t* B = a.B + z0 * a.sB0 + z1 * a.sB1 + col0;
+  gemm_stream_tiles<Cfg>(A, a.lda, B, a.ldb, Cfg::kBN, a.K, nsub, smem, a.C + coff,
                                  a.R ? a.R + coff : nullptr, a.ldc, bias, a.ep.act, tg, a.touch_a ? groups_n : 0);
 }
 
-template <class Cfg, bool PACKED>
+template <class Cfg>
 static nf_status launch_stream(GemmLaunch& L, int nsub, hipStream_t s) {
   GemmArgs& a = L.a;
   if (a.rows % Cfg::kBM || a.cols % Cfg::kBN || a.K % Cfg::kBK || nsub < 1) return NF_EUNSUPPORTED;
   a.tiles_m = a.rows / Cfg::kBM;
   a.tiles_n = a.cols / Cfg::kBN;
   if (a.tiles_n % nsub) return NF_EUNSUPPORTED;
-  if (PACKED) {
-    if (a.panel <= 0 || a.panel % Cfg::kBN || a.cols % a.panel || a.K % 32) return NF_EUNSUPPORTED;
-    // the tiles of a workgroup lie in one panel, or every tile is a panel
-    if (a.panel != Cfg::kBN && a.panel % (nsub * Cfg::kBN)) return NF_EUNSUPPORTED;
-  }
   // the register epilogue moves 16 bytes per lane (output, residual, column constants)
   if (a.ldc % 8 || ((uintptr_t)a.C & 15) || ((uintptr_t)a.R & 15) || ((uintptr_t)a.ep.col_bias & 15) ||
       a.ep.col_vec_stride0 % 4 || a.ep.col_vec_stride1 % 4 || a.sC0 % 8 || a.sC1 % 8)
@@ -63,7 +46,7 @@ static nf_status launch_stream(GemmLaunch& L, int nsub, hipStream_t s) {
   const long long total = (long long)a.tiles_m * (a.tiles_n / nsub) * a.nz0 * L.nz1;
   if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
   a.touch_a = touch_a_pays(total, (long long)a.rows * a.K, (long long)a.nz0 * L.nz1);
-  auto kern = gemm_stream_kernel<Cfg, PACKED>;
+  auto kern = gemm_stream_kernel<Cfg>;
   constexpr int kLds = Cfg::kLdsPipe;
   if (kLds > 64 * 1024) {
     static std::atomic<bool> opted_in{false};
@@ -78,21 +61,16 @@ static nf_status launch_stream(GemmLaunch& L, int nsub, hipStream_t s) {
   return hipGetLastError() == hipSuccess ? NF_OK : NF_ELAUNCH;
 }
 
-template <bool PACKED>
-static nf_status launch_stream_cfg(int cfg, GemmLaunch& L, int nsub, hipStream_t s) {
+nf_status launch_gemm_stream(int cfg, int nsub, GemmLaunch& L, hipStream_t s) {
   switch (cfg) {
-    case S128x96k64: return launch_stream<DmaCfg<128, 96, 64, 4, 3, 5>, PACKED>(L, nsub, s);
-    case S128x128k32: return launch_stream<DmaCfg<128, 128, 32, 2, 4, 8>, PACKED>(L, nsub, s);
-    case S128x288k32: return launch_stream<DmaCfg<128, 288, 32, 4, 3, 5>, PACKED>(L, nsub, s);
-    case S128x384k32: return launch_stream<DmaCfg<128, 384, 32, 2, 6, NF_NS_S384>, PACKED>(L, nsub, s);
-    case S256x256k32: return launch_stream<DmaCfg<256, 256, 32, 2, 4, 4>, PACKED>(L, nsub, s);
-    case S256x128k32: return launch_stream<DmaCfg<256, 128, 32, 4, 2, 6>, PACKED>(L, nsub, s);
+    case S128x96k64: return launch_stream<DmaCfg<128, 96, 64, 4, 3, 5>>(L, nsub, s);
+    case S128x128k32: return launch_stream<DmaCfg<128, 128, 32, 2, 4, 8>>(L, nsub, s);
+    case S128x288k32: return launch_stream<DmaCfg<128, 288, 32, 4, 3, 5>>(L, nsub, s);
+    case S128x384k32: return launch_stream<DmaCfg<128, 384, 32, 2, 6, NF_NS_S384>>(L, nsub, s);
+    case S256x256k32: return launch_stream<DmaCfg<256, 256, 32, 2, 4, 4>>(L, nsub, s);
+    case S256x128k32: return launch_stream<DmaCfg<256, 128, 32, 4, 2, 6>>(L, nsub, s);
   }
   return NF_EUNSUPPORTED;
-}
-
-nf_status launch_gemm_stream(int cfg, int nsub, bool packed, GemmLaunch& L, hipStream_t s) {
-  return packed ? launch_stream_cfg<true>(cfg, L, nsub, s) : launch_stream_cfg<false>(cfg, L, nsub, s);
 }
 
 }  // namespace nf

@@ -17,7 +17,6 @@ struct GemmArgs {
   long sA0, sA1, sB0, sB1, sC0, sC1;      // strides of the two batch coordinates (elements)
   int rows, cols, K, nz0, tiles_m, tiles_n;
   int touch_a;                             // direct-to-LDS kernels: pull the A rows into L2 at kernel start (see touch_a_rows)
-  int panel;                               // block-packed B (netfuse_linear_pack_weight): columns per panel, else 0
   Epilogue ep;
   Im2colGeom geom;                         // implicit-B convolution only
 };
@@ -39,8 +38,6 @@ constexpr int kDmaBN[kNumDmaTiles] = {256, 128, 128, 384, 288, 96};
 constexpr int kDmaBK[kNumDmaTiles] = {32, 32, 64, 32, 32, 64};
 // dense, 16-byte aligned A and B; NF_EUNSUPPORTED if the problem is not a whole number of tiles
 nf_status launch_gemm_dma(int cfg, GemmLaunch& L, hipStream_t s);
-// the same kernels reading a block-packed B operand (L.a.panel columns per panel, a multiple of the tile width)
-nf_status launch_gemm_dma_packed(int cfg, GemmLaunch& L, hipStream_t s);
 
 // Streaming kernels (gemm_stream.h): nsub consecutive column tiles per workgroup through one load pipeline,
 // register epilogue.  Whole-tile problems with 8-byte aligned output rows; NF_EUNSUPPORTED otherwise.
@@ -48,7 +45,17 @@ enum StreamTileId { S128x96k64 = 0, S128x128k32, S128x288k32, S128x384k32, S256x
 constexpr int kStreamBM[kNumStreamTiles] = {128, 128, 128, 128, 256, 256};
 constexpr int kStreamBN[kNumStreamTiles] = {96, 128, 288, 384, 256, 128};
 constexpr int kStreamBK[kNumStreamTiles] = {64, 32, 32, 32, 32, 32};
-nf_status launch_gemm_stream(int cfg, int nsub, bool packed, GemmLaunch& L, hipStream_t s);
+nf_status launch_gemm_stream(int cfg, int nsub, GemmLaunch& L, hipStream_t s);
+
+// Fragment-packed weights (gemm_frag.h): B is the output of launch_pack_fragments, sB0/sB1 its problem strides
+// (K x cols elements per problem); 128-row tiles of 96 / 288 / 384 columns.  NF_EUNSUPPORTED if the problem is
+// not whole tiles, K not a whole number of pipeline rounds, or an operand not 16-byte aligned.
+enum FragTileId { F96 = 0, F288, F384, kNumFragTiles };
+constexpr int kFragBN[kNumFragTiles] = {96, 288, 384};
+constexpr int kFragKUnit[kNumFragTiles] = {256, 128, 128};      // K must be a multiple of this
+nf_status launch_gemm_frag(int cfg, GemmLaunch& L, hipStream_t s);
+// W[problems][K][Nout] -> fragment order (pack_kernels.h); K % 16 == 0, Nout % 32 == 0
+nf_status launch_pack_fragments(const bf16_t* W, bf16_t* Wp, long long problems, int K, int Nout, hipStream_t s);
 
 // BKIND: 8 / 4 / 1 = dense B read with that vector width; 0 = implicit (im2col) B.
 // align_a: 16, 8, 4 or 2 = byte alignment of every A row start (and K a multiple of align_a/2).

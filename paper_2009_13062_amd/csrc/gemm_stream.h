@@ -28,16 +28,16 @@ namespace nf {
 // ends up with 8 consecutive columns: residual and output then move 16 bytes per lane (8-byte stores
 // measured 1.4x the algorithmic write traffic: partially written sectors reaching HBM).
 // Needs 16-byte aligned rows of C and R (ldc % 8 == 0) and a 16-byte aligned column-constant vector.
-template <class Cfg, int ACT>
-__device__ __forceinline__ void stream_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::FN], bf16_t* C, const bf16_t* R,
-                                                    long ldc, const float* col_bias) {
-  constexpr int FM = Cfg::FM, FN = Cfg::FN;
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
+// acc[i][j] is the 32 x 32 block at rows row_base + 32 i, columns col_base + 32 j of the tile that C, R and col_bias
+// point at.
+template <int FM, int FN, int ACT>
+__device__ __forceinline__ void reg_epilogue(f32x16_t (&acc)[FM][FN], bf16_t* C, const bf16_t* R, long ldc,
+                                             const float* col_bias, int row_base, int col_base) {
+  const int lane = threadIdx.x % kWave;
   const int half = lane / 32, l32 = lane % 32;
 #pragma unroll
   for (int j = 0; j < FN; ++j) {
-    const int colb = wn * Cfg::WN + j * 32;
+    const int colb = col_base + j * 32;
     float4 cb[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q)
@@ -45,7 +45,7 @@ __device__ __forceinline__ void stream_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
       // this lane's two 8-column pieces: columns colb + 16 qq + 8 half + 0..7
-      const long off = (long)(wm * Cfg::WM + i * 32 + l32) * ldc + colb + half * 8;
+      const long off = (long)(row_base + i * 32 + l32) * ldc + colb + half * 8;
       uint4 rr[2];
 #pragma unroll
       for (int qq = 0; qq < 2; ++qq)
@@ -85,9 +85,16 @@ __device__ __forceinline__ void stream_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg
   }
 }
 
+template <class Cfg, int ACT>
+__device__ __forceinline__ void stream_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::FN], bf16_t* C, const bf16_t* R,
+                                                    long ldc, const float* col_bias) {
+  const int wave = threadIdx.x / kWave;
+  reg_epilogue<Cfg::FM, Cfg::FN, ACT>(acc, C, R, ldc, col_bias, (wave / Cfg::kWGN) * Cfg::WM, (wave % Cfg::kWGN) * Cfg::WN);
+}
+
 // A, B, C, R, col_bias point at the workgroup's first tile; consecutive tiles are b_tile_stride elements
 // apart in B and Cfg::kBN columns apart in C, R and col_bias.  act is applied before the residual.
-template <class Cfg, bool PACKED>
+template <class Cfg>
 __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, long lda, const bf16_t* __restrict__ B,
                                                   long ldb, long b_tile_stride, int K, int nsub, lds_u8_t* smem,
                                                   bf16_t* C, const bf16_t* R, long ldc, const float* col_bias,
@@ -110,12 +117,6 @@ __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, 
       src[t] = A + (long)row * lda + c * 8;
       inc[t] = BK;
       jump[t] = -(long)(nk - 1) * BK;                        // back to k = 0 of the same rows
-    } else if constexpr (PACKED) {
-      constexpr int kHalves = Cfg::kBN / 16;
-      const int hb = blk - Cfg::kABlocks;
-      src[t] = B + (long)(hb / kHalves) * ldb + (hb % kHalves) * 512 + lane * 8;
-      inc[t] = (long)(BK / 32) * ldb;
-      jump[t] = b_tile_stride - (long)(nk - 1) * inc[t];
     } else {
       const int flat = (blk - Cfg::kABlocks) * 64 + lane;
       const int krow = flat / Cfg::kBCpr;
@@ -162,13 +163,10 @@ __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, 
     for (int hl = 0; hl < 2; ++hl) {
       const int kr = 8 * half + l16 / 4 + 4 * hl;
       const int n = wn * Cfg::WN + j * 32 + ((lane / 16) % 2) * 16 + (l16 % 4) * 4;
-      if constexpr (PACKED)
-        b_off[j][hl] = Cfg::kABytes + (n / 32) * 2048 + kr * 64 + (n % 32) * 2;
-      else
-        b_off[j][hl] = Cfg::kABytes + kr * Cfg::kBRow + (((n / 8) ^ (Cfg::kBSwz * (l16 / 4))) * 16) + ((n / 4) % 2) * 8;
+      b_off[j][hl] = Cfg::kABytes + kr * Cfg::kBRow + (((n / 8) ^ (Cfg::kBSwz * (l16 / 4))) * 16) + ((n / 4) % 2) * 8;
     }
   auto b_step = [](int kk) {
-    return PACKED ? (kk / 2) * (Cfg::kBN / 32) * 2048 + (kk % 2) * 16 * 64 : kk * 16 * Cfg::kBRow;
+    return kk * 16 * Cfg::kBRow;
   };
 
   const int total = nsub * nk;
@@ -205,18 +203,20 @@ __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, 
           bfr[kk][j] = __builtin_bit_cast(bf16x8_t, both);
         }
       }
-      __builtin_amdgcn_sched_barrier(0);
-      wait_lgkmcnt0();
-      __builtin_amdgcn_sched_barrier(0);
-      if (g + NS - 1 < total) issue_stage(g + NS - 1);      // refills the stage read in step g-1
+      // The multiplications start as soon as the fragments of the first 16-k slice are there; the next stage's
+      // loads are issued behind the last slice (they refill the stage read in step g-1).
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kk = 0; kk < BK / 16; ++kk)
+      for (int kk = 0; kk < BK / 16; ++kk) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
           for (int j = 0; j < FN; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (g + NS - 1 < total) issue_stage(g + NS - 1);
+      __builtin_amdgcn_sched_barrier(0);
     }
     const long c0 = (long)sub * Cfg::kBN;
     const float* cb = col_bias ? col_bias + c0 : nullptr;

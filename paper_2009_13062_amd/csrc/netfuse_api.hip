@@ -19,7 +19,6 @@
 #include "generic_kernels.h"
 #include "nf_common.h"
 #include "norm_kernels.h"
-#include "pack_kernels.h"
 
 using namespace nf;
 
@@ -259,7 +258,7 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
     if (bkind == 8 && al == 16) {
       int scfg, snsub;
       if (forced_stream(&scfg, &snsub)) {
-        const nf_status st = launch_gemm_stream(scfg, snsub, false, L, s);
+        const nf_status st = launch_gemm_stream(scfg, snsub, L, s);
         if (st != NF_EUNSUPPORTED) return st;
       }
       const int d = pick_dma_or_small(N, Nout, K, M);
@@ -267,7 +266,7 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
       if (d >= 0) {
         const int sc = pick_stream(d, N, Nout, K, M, act, &snsub);
         if (sc >= 0) {
-          const nf_status st = launch_gemm_stream(sc, snsub, false, L, s);
+          const nf_status st = launch_gemm_stream(sc, snsub, L, s);
           if (st != NF_EUNSUPPORTED) return st;
         }
         return launch_gemm_dma(d, L, s);
@@ -284,83 +283,63 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
   return launched();
 }
 
-int netfuse_linear_packed_panel(int M, int N, int K, int Nout, nf_dtype dt) {
-  if (dt != NF_BF16 || M <= 0 || N <= 0 || K <= 0 || Nout <= 0 || K % 32 != 0 || Nout % 32 != 0) return 0;
-  const int d = pick_dma_or_small(N, Nout, K, M);
-  if (d < 0) return 0;
-  int nsub;
-  const int sc = pick_stream(d, N, Nout, K, M, NF_ACT_NONE, &nsub);      // the activation is not known here
-  return sc >= 0 ? kStreamBN[sc] : kDmaBN[d];
+// The fragment-packed kernel for (N, K, Nout) at M models: the tile width that needs the fewest rounds of
+// workgroups over the 256 compute units, weighted by its width (a round streams width x K weights per unit);
+// ties go to the wider tile.  -1 if no tile fits.
+static int pick_frag(int N, int Nout, int K, int M) {
+  if (N % 128 != 0) return -1;
+  int best = -1;
+  long long best_cost = 0;
+  for (int t = 0; t < kNumFragTiles; ++t) {
+    if (Nout % kFragBN[t] || K % kFragKUnit[t]) continue;
+    const long long tiles = (long long)M * (N / 128) * (Nout / kFragBN[t]);
+    const long long cost = (tiles + 255) / 256 * kFragBN[t];
+    if (best < 0 || cost < best_cost || (cost == best_cost && kFragBN[t] > kFragBN[best])) { best = t; best_cost = cost; }
+  }
+  return best;
 }
 
-nf_status netfuse_linear_pack_weight(const void* W, void* Wp, int M, int K, int Nout, int panel, nf_dtype dt,
-                                     void* stream) {
+int netfuse_linear_packed_supported(int M, int N, int K, int Nout, nf_dtype dt) {
+  if (dt != NF_BF16 || M <= 0 || N <= 0 || K <= 0 || Nout <= 0) return 0;
+  return pick_frag(N, Nout, K, M) >= 0 ? 1 : 0;
+}
+
+nf_status netfuse_linear_pack_weight(const void* W, void* Wp, int M, int K, int Nout, nf_dtype dt, void* stream) {
   if (!W || !Wp || W == Wp) return NF_EINVAL;
-  if (M <= 0 || K <= 0 || Nout <= 0 || panel <= 0 || !is_dtype(dt)) return NF_EINVAL;
-  if (K % 32 != 0 || panel % 32 != 0 || Nout % panel != 0) return NF_EINVAL;
+  if (M <= 0 || K <= 0 || Nout <= 0 || !is_dtype(dt)) return NF_EINVAL;
+  if (K % 16 != 0 || Nout % 32 != 0) return NF_EINVAL;
   const long long total = prod({M, K, Nout});
   if (total >= kMaxElems) return NF_EINVAL;
   if (dt != NF_BF16) return NF_EUNSUPPORTED;
-  if (!aligned(W, 16) || !aligned(Wp, 16)) return NF_EINVAL;
-  const long long chunks = total / 8, blocks = (chunks + 255) / 256;
-  if (blocks > kMaxGrid) return NF_EUNSUPPORTED;
-  nf_launch(pack_weight_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const bf16_t*)W,
-            (bf16_t*)Wp, K, Nout, panel, (size_t)chunks);
-  return launched();
+  if (!aligned(W, 2) || !aligned(Wp, 16)) return NF_EINVAL;
+  return launch_pack_fragments((const bf16_t*)W, (bf16_t*)Wp, M, K, Nout, (hipStream_t)stream);
 }
 
 nf_status netfuse_linear_packed(const void* X, const void* Wp, const float* bias, const void* residual, void* Y,
-                                int M, int N, int K, int Nout, int panel, nf_dtype dt, nf_act act, void* stream) {
+                                int M, int N, int K, int Nout, nf_dtype dt, nf_act act, void* stream) {
   if (!X || !Wp || !Y) return NF_EINVAL;
-  if (M <= 0 || N <= 0 || K <= 0 || Nout <= 0 || panel <= 0) return NF_EINVAL;
+  if (M <= 0 || N <= 0 || K <= 0 || Nout <= 0) return NF_EINVAL;
   if (!is_dtype(dt) || !is_act(act)) return NF_EINVAL;
-  if (K % 32 != 0 || panel % 32 != 0 || Nout % panel != 0) return NF_EINVAL;
+  if (K % 16 != 0 || Nout % 32 != 0) return NF_EINVAL;
   if (prod({M, N, K}) >= kMaxElems || prod({M, K, Nout}) >= kMaxElems || prod({M, N, Nout}) >= kMaxElems)
     return NF_EINVAL;
   if (dt != NF_BF16) return NF_EUNSUPPORTED;
   if (!aligned(X, 2) || !aligned(Wp, 16) || !aligned(Y, 2) || !aligned(residual, 2) || !aligned(bias, 4))
     return NF_EINVAL;
-  if (!aligned(X, 16) || K % 8 != 0) return NF_EUNSUPPORTED;
-  // the widest direct-to-LDS tile of this shape class whose width divides the panel
-  int d = pick_dma_or_small(N, Nout, K, M);
-  if (d == kPreferSmallTile) d = pick_dma(N, Nout, K, M);
-  if (d < 0 || panel % kDmaBN[d] != 0) {
-    d = -1;
-    long long best = 0;
-    for (int t = 0; t < kNumDmaTiles; ++t) {
-      if (N % kDmaBM[t] || Nout % kDmaBN[t] || K % kDmaBK[t] || panel % kDmaBN[t]) continue;
-      const long long tiles = (long long)M * (N / kDmaBM[t]) * (Nout / kDmaBN[t]);
-      const long long cost = (tiles + 255) / 256 * ((long long)kDmaBM[t] + kDmaBN[t]) * K;
-      if (d < 0 || cost < best) { d = t; best = cost; }
-    }
-    if (d < 0) return NF_EUNSUPPORTED;
-  }
+  const int f = pick_frag(N, Nout, K, M);
+  if (f < 0) return NF_EUNSUPPORTED;
   GemmLaunch L;
   memset(&L, 0, sizeof(L));
   GemmArgs& a = L.a;
   a.A = (const bf16_t*)X; a.B = (const bf16_t*)Wp; a.R = (const bf16_t*)residual; a.C = (bf16_t*)Y;
   a.B_end = a.B + (long long)M * K * Nout;
-  a.lda = K; a.ldb = 0; a.ldc = Nout; a.panel = panel;
+  a.lda = K; a.ldb = 0; a.ldc = Nout;
   a.sA0 = (long)N * K; a.sB0 = (long)K * Nout; a.sC0 = (long)N * Nout;
   a.rows = N; a.cols = Nout; a.K = K; a.nz0 = M;
   L.nz1 = 1;
   a.ep.col_bias = bias; a.ep.col_vec_stride0 = Nout;
   a.ep.act = act; a.ep.act_before_residual = 1;
-  a.ep.vec_store = Nout % 8 == 0 && aligned(Y, 16) && aligned(residual, 16) ? 2
-                   : Nout % 4 == 0 && aligned(Y, 8) && aligned(residual, 8) ? 1 : 0;
-  int scfg, snsub;
-  if (forced_stream(&scfg, &snsub)) {
-    const nf_status st = launch_gemm_stream(scfg, snsub, true, L, (hipStream_t)stream);
-    if (st != NF_EUNSUPPORTED) return st;
-  }
-  {
-    const int sc = pick_stream(d, N, Nout, K, M, act, &snsub);
-    if (sc >= 0 && panel % kStreamBN[sc] == 0) {
-      const nf_status st = launch_gemm_stream(sc, snsub, true, L, (hipStream_t)stream);
-      if (st != NF_EUNSUPPORTED) return st;
-    }
-  }
-  return launch_gemm_dma_packed(d, L, (hipStream_t)stream);
+  return launch_gemm_frag(f, L, (hipStream_t)stream);
 }
 
 nf_status netfuse_linear_ragged(const void* X, const void* W, const float* bias, void* Y, int M, int N, int K,

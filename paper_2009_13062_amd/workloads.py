@@ -30,11 +30,22 @@ class EncoderStack:
 
     def __init__(self, layers: List[Dict[str, torch.Tensor]], M: int, batch: int, seq: int, heads: int,
                  eps: float = 1e-5, buffers: Optional[Dict[str, torch.Tensor]] = None,
-                 R: Optional[torch.Tensor] = None):
+                 R: Optional[torch.Tensor] = None, packed: bool = False):
         """R[2*seq, hidden] (relative position encodings) switches the attention to the relative-position form
-        (XLNet-shaped layers): per layer Kr = R Wr (one more merged matmul) and the query biases rwb, rrb."""
+        (XLNet-shaped layers): per layer Kr = R Wr (one more merged matmul) and the query biases rwb, rrb.
+        packed: re-lay the weight matrices out once (netfuse_linear_pack_weight) and run the matmuls that have a
+        packed kernel through netfuse_linear_packed; the packed copies are kept beside the originals under
+        the key + "_p"."""
         self.layers, self.M, self.batch, self.seq, self.heads, self.eps = layers, M, batch, seq, heads, eps
         self.R = R
+        self.packed = packed
+        if packed:
+            for Lw in layers:
+                for k in self.MATS:
+                    if k in Lw and k + "_p" not in Lw:
+                        rows = 2 * seq if k == "Wr" else batch * seq
+                        if nf.linear_packed_supported(M, rows, Lw[k].shape[1], Lw[k].shape[2], Lw[k].dtype):
+                            Lw[k + "_p"] = nf.linear_pack_weight(Lw[k])
         W = layers[0]
         self.hidden, self.ffn = W["Wqkv"].shape[1], W["W1"].shape[2]
         N, Hd, F = batch * seq, self.hidden, self.ffn
@@ -49,26 +60,31 @@ class EncoderStack:
         self.buf = buffers
 
     @classmethod
-    def from_numpy(cls, inp, M, batch, seq, heads, dtype=torch.bfloat16, eps=1e-5):
+    def from_numpy(cls, inp, M, batch, seq, heads, dtype=torch.bfloat16, eps=1e-5, packed=False):
         layers = []
         for Lw in inp["layers"]:
             layers.append({k: to_device(v, dtype if k in cls.MATS else torch.float32) for k, v in Lw.items()})
         R = to_device(inp["R"], dtype) if "R" in inp else None
-        return cls(layers, M, batch, seq, heads, eps, R=R)
+        return cls(layers, M, batch, seq, heads, eps, R=R, packed=packed)
+
+    def _linear(self, X, Lw, key, **kw):
+        if self.packed and key + "_p" in Lw:
+            return nf.linear_packed(X, Lw[key + "_p"], **kw)
+        return nf.linear(X, Lw[key], **kw)
 
     def layer(self, X, Lw, out, trace=None):
         b, M = self.buf, self.M
-        nf.linear(X, Lw["Wqkv"], bias=Lw["bqkv"], out=b["qkv"])
+        self._linear(X, Lw, "Wqkv", bias=Lw["bqkv"], out=b["qkv"])
         if self.R is None:
             nf.attention_packed(b["qkv"], self.batch, self.seq, self.heads, out=b["att"])
         else:
-            nf.linear(b["Rrep"], Lw["Wr"], out=b["kr"])
+            self._linear(b["Rrep"], Lw, "Wr", out=b["kr"])
             nf.attention_relpos_packed(b["qkv"], b["kr"], self.batch, self.seq, self.heads, bias_w=Lw["rwb"],
                                        bias_r=Lw["rrb"], out=b["att"])
-        nf.linear(b["att"], Lw["Wo"], bias=Lw["bo"], residual=X, out=b["h"])
+        self._linear(b["att"], Lw, "Wo", bias=Lw["bo"], residual=X, out=b["h"])
         nf.layernorm(b["h"], Lw["ln1_g"], Lw["ln1_b"], M, eps=self.eps, out=b["x1"])
-        nf.linear(b["x1"], Lw["W1"], bias=Lw["b1"], act=nf.ACT_GELU, out=b["f1"])
-        nf.linear(b["f1"], Lw["W2"], bias=Lw["b2"], residual=b["x1"], out=b["f2"])
+        self._linear(b["x1"], Lw, "W1", bias=Lw["b1"], act=nf.ACT_GELU, out=b["f1"])
+        self._linear(b["f1"], Lw, "W2", bias=Lw["b2"], residual=b["x1"], out=b["f2"])
         nf.layernorm(b["f2"], Lw["ln2_g"], Lw["ln2_b"], M, eps=self.eps, out=out)
         if trace is not None:
             keys = ("qkv", "att", "h", "x1", "f1", "f2") + (("kr",) if self.R is not None else ())
@@ -81,7 +97,9 @@ class EncoderStack:
             X = self.layer(X, Lw, outs[i % 2], trace)
         return X
 
-    def per_model(self):
+    def per_model(self, packed: bool = False):
+        """One single-model stack per model on slices of the same tensors.  By default they call netfuse_linear
+        on the unpacked weights, whose tile rules know about single models."""
         Hd = self.hidden
         out = []
         for m in range(self.M):
@@ -92,7 +110,8 @@ class EncoderStack:
                     d[k] = v[m * Hd:(m + 1) * Hd] if k.startswith("ln") else v[m:m + 1]
                 layers.append(d)
             bufs = {k: v[m:m + 1] for k, v in self.buf.items()}
-            out.append(EncoderStack(layers, 1, self.batch, self.seq, self.heads, self.eps, bufs, R=self.R))
+            out.append(EncoderStack(layers, 1, self.batch, self.seq, self.heads, self.eps, bufs, R=self.R,
+                                    packed=packed and self.packed))
         return out
 
 

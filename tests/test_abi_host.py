@@ -61,28 +61,30 @@ def test_linear_rejects_bad_arguments(lib):
 
 
 def test_packed_linear_rejects_bad_arguments(lib):
-    pk, run, width = lib.netfuse_linear_pack_weight, lib.netfuse_linear_packed, lib.netfuse_linear_packed_panel
-    for bad in ((None, 2 * P, 2, 64, 96, 96, 1), (P, None, 2, 64, 96, 96, 1), (P, P, 2, 64, 96, 96, 1),
-                (P, 2 * P, 0, 64, 96, 96, 1), (P, 2 * P, 2, 60, 96, 96, 1), (P, 2 * P, 2, 64, 96, 64, 1),
-                (P, 2 * P, 2, 64, 96, 48, 1), (P, 2 * P, 2, 64, 96, 96, 5), (P + 2, 2 * P, 2, 64, 96, 96, 1)):
+    pk, run, can = lib.netfuse_linear_pack_weight, lib.netfuse_linear_packed, lib.netfuse_linear_packed_supported
+    for bad in ((None, 2 * P, 2, 64, 96, 1), (P, None, 2, 64, 96, 1), (P, P, 2, 64, 96, 1),
+                (P, 2 * P, 0, 64, 96, 1), (P, 2 * P, 2, 60, 96, 1), (P, 2 * P, 2, 64, 80, 1),
+                (P, 2 * P, 2, 64, 96, 5), (P + 1, 2 * P, 2, 64, 96, 1), (P, 2 * P + 8, 2, 64, 96, 1)):
         assert pk(*bad, None) == EINVAL, bad
-    assert pk(P, 2 * P, 2, 64, 96, 96, 0, None) == 2                   # float storage: no packed kernel
-    ok = dict(X=P, W=P, bias=None, res=None, Y=P, M=2, N=128, K=64, Nout=96, panel=96, dt=1, act=0)
+    assert pk(P, 2 * P, 2, 64, 96, 0, None) == 2                       # float storage: no packed kernel
+    ok = dict(X=P, W=P, bias=None, res=None, Y=P, M=2, N=128, K=256, Nout=96, dt=1, act=0)
 
     def call(**kw):
         a = dict(ok, **kw)
-        return run(a["X"], a["W"], a["bias"], a["res"], a["Y"], a["M"], a["N"], a["K"], a["Nout"], a["panel"],
+        return run(a["X"], a["W"], a["bias"], a["res"], a["Y"], a["M"], a["N"], a["K"], a["Nout"],
                    a["dt"], a["act"], None)
 
-    for bad in (dict(X=None), dict(W=None), dict(Y=None), dict(M=0), dict(N=0), dict(K=48), dict(panel=0),
-                dict(panel=64), dict(dt=3), dict(act=7), dict(W=P + 2), dict(bias=P + 1)):
+    for bad in (dict(X=None), dict(W=None), dict(Y=None), dict(M=0), dict(N=0), dict(K=40), dict(Nout=80),
+                dict(dt=3), dict(act=7), dict(W=P + 2), dict(bias=P + 1)):
         assert call(**bad) == EINVAL, bad
     assert call(dt=0) == 2
     assert call(N=100) == 2                                             # not whole tiles: NF_EUNSUPPORTED
-    # the panel query: bf16 whole-tile shapes only, and a width that divides Nout
-    assert width(32, 128, 768, 3072, 1) in (96, 128, 192, 256, 288, 384)
-    assert 3072 % width(32, 128, 768, 3072, 1) == 0
-    assert width(32, 128, 768, 3072, 0) == 0 and width(32, 100, 768, 3072, 1) == 0 and width(0, 128, 768, 768, 1) == 0
+    assert call(K=64) == 2                                              # shorter than one round of the pipeline
+    assert call(Nout=128) == 2                                          # no tile width divides it
+    # the query agrees with what the call accepts
+    assert can(32, 128, 768, 3072, 1) == 1 and can(32, 128, 3072, 768, 1) == 1 and can(2, 256, 128, 288, 1) == 1
+    assert can(32, 128, 768, 3072, 0) == 0 and can(32, 100, 768, 3072, 1) == 0 and can(0, 128, 768, 768, 1) == 0
+    assert can(2, 128, 64, 96, 1) == 0 and can(2, 128, 256, 128, 1) == 0
 
 
 def test_ragged_linear_rejects_bad_arguments(lib):
