@@ -10,7 +10,7 @@
 
 namespace nf {
 
-template <class Cfg>
+template <class Cfg, bool PB>
 __global__ __launch_bounds__(Cfg::kThreads) void gemm_stream_kernel(GemmArgs a, int nsub) {
   extern __shared__ __align__(1024) unsigned char smem_raw[];
   lds_u8_t* smem = (lds_u8_t*)smem_raw;
@@ -25,12 +25,13 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_stream_kernel(GemmArgs a, 
   const long coff = z0 * a.sC0 + z1 * a.sC1 + (long)row0 * a.ldc + col0;
   const bf16_t* A = a.A + z0 * a.sA0 + z1 * a.sA1 + (long)row0 * a.lda;
   const float* bias = a.ep.col_bias ? a.ep.col_bias + z0 * a.ep.col_vec_stride0 + z1 * a.ep.col_vec_stride1 + col0 : nullptr;
-  const bf16_t* B = a.B + z0 * a.sB0 + z1 * a.sB1 + col0;
-  gemm_stream_tiles<Cfg>(A, a.lda, B, a.ldb, Cfg::kBN, a.K, nsub, smem, a.C + coff,
-                                 a.R ? a.R + coff : nullptr, a.ldc, bias, a.ep.act, tg, a.touch_a ? groups_n : 0);
+  // row-major weights: column col0 of row 0; fragment-packed: column block col0 / 32 (K/16 fragments of 512 elements each)
+  const bf16_t* B = a.B + z0 * a.sB0 + z1 * a.sB1 + (PB ? (long)(col0 / 32) * a.K * 32 : (long)col0);
+  gemm_stream_tiles<Cfg, PB>(A, a.lda, B, a.ldb, PB ? (long)Cfg::kBN * a.K : (long)Cfg::kBN, a.K, nsub, smem, a.C + coff,
+                             a.R ? a.R + coff : nullptr, a.ldc, bias, a.ep.act, tg, a.touch_a ? groups_n : 0);
 }
 
-template <class Cfg>
+template <class Cfg, bool PB = false>
 static nf_status launch_stream(GemmLaunch& L, int nsub, hipStream_t s) {
   GemmArgs& a = L.a;
   if (a.rows % Cfg::kBM || a.cols % Cfg::kBN || a.K % Cfg::kBK || nsub < 1) return NF_EUNSUPPORTED;
@@ -46,7 +47,9 @@ static nf_status launch_stream(GemmLaunch& L, int nsub, hipStream_t s) {
   const long long total = (long long)a.tiles_m * (a.tiles_n / nsub) * a.nz0 * L.nz1;
   if (total <= 0 || total > 0x7fffffffLL) return NF_EUNSUPPORTED;
   a.touch_a = touch_a_pays(total, (long long)a.rows * a.K, (long long)a.nz0 * L.nz1);
-  auto kern = gemm_stream_kernel<Cfg>;
+  if (PB && (a.K % 16 || ((uintptr_t)a.B & 15) || a.sB0 % 8 || a.sB1 % 8 || a.lda % 8 || ((uintptr_t)a.A & 15) || a.sA0 % 8 || a.sA1 % 8))
+    return NF_EUNSUPPORTED;
+  auto kern = gemm_stream_kernel<Cfg, PB>;
   constexpr int kLds = Cfg::kLdsPipe;
   if (kLds > 64 * 1024) {
     static std::atomic<bool> opted_in{false};
@@ -71,6 +74,10 @@ nf_status launch_gemm_stream(int cfg, int nsub, GemmLaunch& L, hipStream_t s) {
     case S256x128k32: return launch_stream<DmaCfg<256, 128, 32, 4, 2, 6>>(L, nsub, s);
   }
   return NF_EUNSUPPORTED;
+}
+
+nf_status launch_gemm_stream_packed(int nsub, GemmLaunch& L, hipStream_t s) {
+  return launch_stream<DmaCfg<256, 256, 32, 2, 4, 4>, true>(L, nsub, s);
 }
 
 }  // namespace nf

@@ -46,6 +46,9 @@ constexpr int kStreamBM[kNumStreamTiles] = {128, 128, 128, 128, 256, 256};
 constexpr int kStreamBN[kNumStreamTiles] = {96, 128, 288, 384, 256, 128};
 constexpr int kStreamBK[kNumStreamTiles] = {64, 32, 32, 32, 32, 32};
 nf_status launch_gemm_stream(int cfg, int nsub, GemmLaunch& L, hipStream_t s);
+// The 256 x 256 streaming kernel on fragment-packed weights (B = output of launch_pack_fragments, sB0/sB1 its
+// problem strides): rows and columns multiples of 256, K of 32, everything 16-byte aligned.
+nf_status launch_gemm_stream_packed(int nsub, GemmLaunch& L, hipStream_t s);
 
 // Fragment-packed weights (gemm_frag.h): B is the output of launch_pack_fragments, sB0/sB1 its problem strides
 // (K x cols elements per problem); 128-row tiles of 96 / 288 / 384 columns.  NF_EUNSUPPORTED if the problem is

@@ -58,8 +58,10 @@ __device__ __forceinline__ void reg_epilogue(f32x16_t (&acc)[FM][FN], bf16_t* C,
           // group 2 qq + half stays (its other half comes from the partner), group 2 qq + 1 - half is sent
           const float b0[4] = {cb[2 * qq].x, cb[2 * qq].y, cb[2 * qq].z, cb[2 * qq].w};
           const float b1[4] = {cb[2 * qq + 1].x, cb[2 * qq + 1].y, cb[2 * qq + 1].z, cb[2 * qq + 1].w};
-          const float v0 = act_const<ACT>(fmaf(acc[i][j][(2 * qq) * 4 + e] + b0[e] + 0.f, 1.f, 0.f));
-          const float v1 = act_const<ACT>(fmaf(acc[i][j][(2 * qq + 1) * 4 + e] + b1[e] + 0.f, 1.f, 0.f));
+          // (an accumulator is never -0 -- it starts at +0 and (+0) + (-0) = +0 -- so neither is the sum, and the
+          // "+ 0, x 1 + 0" steps with which the other epilogues normalise a -0 would change no bit here)
+          const float v0 = act_const<ACT>(acc[i][j][(2 * qq) * 4 + e] + b0[e]);
+          const float v1 = act_const<ACT>(acc[i][j][(2 * qq + 1) * 4 + e] + b1[e]);
           own[e] = half ? v1 : v0;
           send[e] = half ? v0 : v1;
         }
@@ -94,7 +96,13 @@ __device__ __forceinline__ void stream_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg
 
 // A, B, C, R, col_bias point at the workgroup's first tile; consecutive tiles are b_tile_stride elements
 // apart in B and Cfg::kBN columns apart in C, R and col_bias.  act is applied before the residual.
-template <class Cfg>
+//
+// PB (fragment-packed weights, pack_kernels.h): B points at the first fragment of the workgroup's first column
+// block; a stage's B part is the (BN / 32) x (BK / 16) fragments of 1 KB of the tile's column blocks and the
+// stage's k slices, each fetched by one direct-to-LDS load (64 lanes x 16 contiguous bytes) and read back as it
+// lies with one 16-byte LDS read per lane: no transposing read (a third of the rate of 16-byte reads) and
+// no bank conflicts by construction.  ldb is unused; b_tile_stride = BN x K elements.
+template <class Cfg, bool PB = false>
 __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, long lda, const bf16_t* __restrict__ B,
                                                   long ldb, long b_tile_stride, int K, int nsub, lds_u8_t* smem,
                                                   bf16_t* C, const bf16_t* R, long ldc, const float* col_bias,
@@ -117,6 +125,11 @@ __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, 
       src[t] = A + (long)row * lda + c * 8;
       inc[t] = BK;
       jump[t] = -(long)(nk - 1) * BK;                        // back to k = 0 of the same rows
+    } else if constexpr (PB) {
+      const int bb = blk - Cfg::kABlocks;                    // fragment (column block bb / (BK/16), slice bb % (BK/16))
+      src[t] = B + ((long)(bb / (BK / 16)) * (K / 16) + bb % (BK / 16)) * 512 + lane * 8;
+      inc[t] = (BK / 16) * 512;
+      jump[t] = b_tile_stride - (long)(nk - 1) * inc[t];
     } else {
       const int flat = (blk - Cfg::kABlocks) * 64 + lane;
       const int krow = flat / Cfg::kBCpr;
@@ -168,6 +181,9 @@ __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, 
   auto b_step = [](int kk) {
     return kk * 16 * Cfg::kBRow;
   };
+  int bp_off[FN];                                            // PB: this lane's 16 bytes of column block j, slice 0
+#pragma unroll
+  for (int j = 0; j < FN; ++j) bp_off[j] = Cfg::kABytes + (wn * FN + j) * (BK / 16) * 1024 + lane * 16;
 
   const int total = nsub * nk;
 #pragma unroll
@@ -197,10 +213,14 @@ __device__ __forceinline__ void gemm_stream_tiles(const bf16_t* __restrict__ A, 
           af[kk][i] = *(const lds_bf16x8_t*)(stage + a_off[i] + (((2 * kk + half) ^ a_swz) * 16));
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
-          const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][0] + b_step(kk)));
-          const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][1] + b_step(kk)));
-          const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          bfr[kk][j] = __builtin_bit_cast(bf16x8_t, both);
+          if constexpr (PB) {
+            bfr[kk][j] = *(const lds_bf16x8_t*)(stage + bp_off[j] + kk * 1024);
+          } else {
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][0] + b_step(kk)));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_t*)(stage + b_off[j][1] + b_step(kk)));
+            const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            bfr[kk][j] = __builtin_bit_cast(bf16x8_t, both);
+          }
         }
       }
       // The multiplications start as soon as the fragments of the first 16-k slice are there; the next stage's

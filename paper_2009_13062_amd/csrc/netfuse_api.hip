@@ -299,9 +299,34 @@ static int pick_frag(int N, int Nout, int K, int M) {
   return best;
 }
 
+// The 256 x 256 streaming kernel on packed weights (several column tiles per workgroup through one pipeline;
+// gemm_stream.h).  It takes the shapes the 128-row fragment kernel has no tile for (output widths that are
+// multiples of 256 but not of 96, 288 or 384), and it is preferred where it measured faster: with a GELU
+// epilogue and at least three tiles per compute unit (768 -> 3072 at 512 rows and 32 models: 102 against 107 us;
+// without the GELU the fragment kernel is ahead: 75 against 88, 82 against 98, 32 against 39 us on the other
+// three encoder shapes).  Returns the number of column tiles per workgroup, 0 = not applicable.
+static int pick_packed_stream(int N, int Nout, int K, int M, int act, bool* preferred) {
+  *preferred = false;
+  if (N % 256 || Nout % 256 || K % 32) return 0;
+  const int tn = Nout / 256;
+  const long long tiles = (long long)M * (N / 256) * tn;
+  // tiles a compute unit works through one after the other = rounds of workgroups x tiles per workgroup;
+  // ties go to more tiles per workgroup (one launch ramp, epilogues under the next tile's loads)
+  int best = 1;
+  long long best_cost = 0;
+  for (int n = 1; n <= tn; ++n) {
+    if (tn % n) continue;
+    const long long cost = ((tiles / n + 255) / 256) * n;
+    if (n == 1 || cost <= best_cost) { best = n; best_cost = cost; }
+  }
+  *preferred = act == NF_ACT_GELU && tiles >= 3 * 256;
+  return best;
+}
+
 int netfuse_linear_packed_supported(int M, int N, int K, int Nout, nf_dtype dt) {
   if (dt != NF_BF16 || M <= 0 || N <= 0 || K <= 0 || Nout <= 0) return 0;
-  return pick_frag(N, Nout, K, M) >= 0 ? 1 : 0;
+  bool pref;
+  return pick_frag(N, Nout, K, M) >= 0 || pick_packed_stream(N, Nout, K, M, NF_ACT_NONE, &pref) > 0 ? 1 : 0;
 }
 
 nf_status netfuse_linear_pack_weight(const void* W, void* Wp, int M, int K, int Nout, nf_dtype dt, void* stream) {
@@ -327,7 +352,9 @@ nf_status netfuse_linear_packed(const void* X, const void* Wp, const float* bias
   if (!aligned(X, 2) || !aligned(Wp, 16) || !aligned(Y, 2) || !aligned(residual, 2) || !aligned(bias, 4))
     return NF_EINVAL;
   const int f = pick_frag(N, Nout, K, M);
-  if (f < 0) return NF_EUNSUPPORTED;
+  bool ps_preferred;
+  const int ps = pick_packed_stream(N, Nout, K, M, act, &ps_preferred);
+  if (f < 0 && ps <= 0) return NF_EUNSUPPORTED;
   GemmLaunch L;
   memset(&L, 0, sizeof(L));
   GemmArgs& a = L.a;
@@ -339,6 +366,11 @@ nf_status netfuse_linear_packed(const void* X, const void* Wp, const float* bias
   L.nz1 = 1;
   a.ep.col_bias = bias; a.ep.col_vec_stride0 = Nout;
   a.ep.act = act; a.ep.act_before_residual = 1;
+  if (ps > 0 && (ps_preferred || f < 0)) {
+    a.ep.vec_store = 2;
+    const nf_status st = launch_gemm_stream_packed(ps, L, (hipStream_t)stream);
+    if (st != NF_EUNSUPPORTED || f < 0) return st;
+  }
   return launch_gemm_frag(f, L, (hipStream_t)stream);
 }
 

@@ -42,6 +42,13 @@ PACKED_CASES = [
     (3, 128, 128, 288, False, False, 0),      # K = one round at k-steps of 32
     (5, 128, 512, 384, True, True, 2),
     (2, 128, 768, 2304, True, False, 0),      # few models
+    # 256 rows per model and more, 256-column multiples: 256 x 256 tiles with the packed fragments staged through LDS
+    (32, 512, 768, 3072, True, False, 2),     # three column tiles per workgroup, GELU
+    (32, 512, 768, 2304, True, False, 0),     # three column tiles per workgroup
+    (32, 512, 3072, 768, True, True, 0),      # one tile per workgroup, long k, residual
+    (2, 256, 64, 512, True, True, 1),         # only this kernel fits 512 columns; K shorter than the pipeline
+    (3, 256, 96, 1024, False, True, 2),
+    (1, 768, 160, 256, True, False, 0),       # three row tiles of one model
 ]
 
 
