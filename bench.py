@@ -449,6 +449,36 @@ def micro_norms(torch, nf, events):
     return out
 
 
+def measured_peaks(torch, nf, events):
+    """What this device reaches on the two roofs, measured like the operators (kernel begin/end timestamps): the
+    issue rate of the bf16 matrix instruction from registers, a read-only stream over 2 GiB, and a plain copy."""
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    out = {}
+
+    def best_us(fn, reps=7):
+        us = []
+        for _ in range(reps):
+            s, e = events.get(), events.get()
+            nf.time_next_launch(s, e)
+            fn()
+            torch.cuda.synchronize()
+            us.append(1e3 * events.ms(s, e))
+            events.release(s, e)
+        return min(us[1:])
+    box = {}
+    us = best_us(lambda: box.__setitem__("fl", nf.probe_mfma(sink, 4000)))
+    out["mfma_bf16_TFLOPs"] = box["fl"] / (us * 1e-6) / 1e12
+    buf = torch.empty(1 << 30, dtype=torch.int16, device="cuda").zero_()          # 2 GiB: eight times the memory-side cache
+    us = best_us(lambda: box.__setitem__("by", nf.probe_hbm_read(buf, sink)))
+    out["hbm_read_GBps"] = box["by"] / (us * 1e-6) / 1e9
+    src = buf[: 1 << 29].view(1, 1 << 18, 2048).view(torch.bfloat16)
+    dst = buf[1 << 29:].view(1 << 18, 2048).view(torch.bfloat16)
+    us = best_us(lambda: nf.merge_transpose(src, 1, True, out=dst))
+    out["hbm_copy_GBps"] = 2 * src.numel() * 2 / (us * 1e-6) / 1e9                # bytes read + bytes written
+    out["datasheet"] = {"mfma_bf16_TFLOPs": MFMA_BF16_PEAK / 1e12, "hbm_GBps": HBM_PEAK / 1e9}
+    return out
+
+
 def cpu_baseline(name):
     """The oracle as it stands, on the host cores, on a bounded sample of the same workload."""
     import netfuse_inputs as NI
@@ -495,7 +525,7 @@ def main():
     ap.add_argument("--quick", action="store_true", help="headline workload only: no sweeps, no other workloads, no CPU baseline")
     ap.add_argument("--no-separate", action="store_true", help="skip the M-separate-launches leg (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true", help="only run a plain copy of known size and exit")
-    ap.add_argument("--micro", default="", choices=["", "norms"], help="only the named micro-benchmark leg")
+    ap.add_argument("--micro", default="", choices=["", "norms", "peaks"], help="only the named micro-benchmark leg")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (models are independent: sharding M over GPUs needs no "
@@ -514,6 +544,9 @@ def main():
         return
     if args.micro == "norms":
         print(json.dumps({"norm_kernels": micro_norms(torch, nf, events)}))
+        return
+    if args.micro == "peaks":
+        print(json.dumps({"measured_peaks": measured_peaks(torch, nf, events)}))
         return
     use_graph = not args.no_graph
     sweep_steps = max(5, min(args.steps, 30))
@@ -546,10 +579,12 @@ def main():
             except Exception as ex:
                 others[name] = dict(error=repr(ex)[:300])
                 log("[bench] %s failed: %r" % (name, ex))
-    norms = None
+    norms = peaks = None
     if not args.quick:
         torch.cuda.empty_cache()
         norms = micro_norms(torch, nf, events)
+        peaks = measured_peaks(torch, nf, events)
+        torch.cuda.empty_cache()
     cpu = None
     if not (args.quick or args.no_cpu_baseline):
         cpu = cpu_baseline(args.workload)
@@ -557,6 +592,12 @@ def main():
 
     kind, M, _ = WORKLOADS[args.workload]
     rf = head["roofline"]
+    rf = dict(rf)
+    if peaks:
+        # beside the fractions of the datasheet peaks: the same against what this device measures on a pure
+        # matrix-instruction loop and on a pure read stream
+        rf["frac_of_measured_hbm_read"] = rf["frac_hbm"] * HBM_PEAK / 1e9 / peaks["hbm_read_GBps"]
+        rf["frac_of_measured_mfma"] = rf["frac_mfma"] * MFMA_BF16_PEAK / 1e12 / peaks["mfma_bf16_TFLOPs"]
     line = {
         "metric": "merged inferences/sec at M=%d (one %s per model), vs M separate launches" % (
             M, "sequence" if kind == "encoder" else "image"),
@@ -573,11 +614,13 @@ def main():
         "kernel_time_ms_per_step": head["kernel_time_ms_per_step"],
         "roofline": {k: rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel", "launches",
                                         "avg_us", "bytes_per_launch", "flops_per_launch", "frac_hbm", "frac_mfma",
-                                        "frac_of_min_roof", "timing")},
+                                        "frac_of_min_roof", "frac_of_measured_hbm_read", "frac_of_measured_mfma",
+                                        "timing") if k in rf},
         "kernels": head["kernels"],
         "cpu_baseline": cpu,
         **sweeps,
         "norm_kernels": norms,
+        "measured_peaks": peaks,
         "other_workloads": others,
         "paper_context": "NetFuse reports up to 3.6x (V100) / 3.0x (TITAN Xp) over its best baseline at 32 instances, fp32, bs 1",
     }

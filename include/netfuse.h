@@ -209,6 +209,19 @@ nf_status netfuse_merge_transpose(const void* src, void* dst, int M, int rows, i
  */
 nf_status netfuse_time_next_launch(void* start_event, void* stop_event);
 
+/*
+ * Measured roofs (the merged operators are priced against the matrix pipe and against HBM; Section 5.1
+ * measures on the machine at hand): two kernels that do nothing but the limiting operation, launched
+ * and timed like any operator (netfuse_time_next_launch applies to them).
+ * netfuse_probe_mfma: `iters` rounds of four independent 32x32x16 bf16 matrix instructions per wavefront, from
+ *   registers only, on 256 workgroups of 16 wavefronts; *flops (HOST pointer) receives the floating point
+ *   operations the launch executes.  sink: 4 device bytes, never written.
+ * netfuse_probe_hbm_read: reads src[0 .. bytes) (device, 16-byte aligned, bytes a multiple of 16) once with
+ *   16-byte non-temporal loads and discards it.  sink: 4 device bytes, never written.
+ */
+nf_status netfuse_probe_mfma(void* sink, int iters, double* flops, void* stream);
+nf_status netfuse_probe_hbm_read(const void* src, long long bytes, void* sink, void* stream);
+
 /* Static description of a status code; never NULL. */
 const char* netfuse_strerror(nf_status status);
 

@@ -28,7 +28,7 @@ EXPORTS = ("netfuse_linear", "netfuse_conv2d", "netfuse_layernorm", "netfuse_bat
            "netfuse_bn_fold", "netfuse_attention", "netfuse_maxpool2d", "netfuse_avgpool_global",
            "netfuse_merge_transpose", "netfuse_linear_pack_weight", "netfuse_linear_packed",
            "netfuse_time_next_launch", "netfuse_linear_packed_supported", "netfuse_linear_ragged",
-           "netfuse_attention_relpos", "netfuse_strerror")
+           "netfuse_attention_relpos", "netfuse_probe_mfma", "netfuse_probe_hbm_read", "netfuse_strerror")
 
 
 class NetFuseError(RuntimeError):
@@ -59,6 +59,8 @@ def _load() -> ctypes.CDLL:
     lib.netfuse_time_next_launch.argtypes = [vp, vp]
     lib.netfuse_attention_relpos.argtypes = [vp, vp, vp, vp, fp, fp, fp, vp, i, i, i, i, i, l, l, f, i, vp]
     lib.netfuse_linear_ragged.argtypes = [vp, vp, fp, vp, i, i, i, ctypes.POINTER(ctypes.c_int), i, i, vp]
+    lib.netfuse_probe_mfma.argtypes = [vp, i, ctypes.POINTER(ctypes.c_double), vp]
+    lib.netfuse_probe_hbm_read.argtypes = [vp, ctypes.c_longlong, vp, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.netfuse_strerror.argtypes = [ctypes.c_int]
@@ -169,6 +171,20 @@ def ragged_views(flat, rows, nout):
 def time_next_launch(start_event, stop_event):
     """Arm the next kernel launch of this thread with two raw hipEvent_t handles (ints or None)."""
     _check("netfuse_time_next_launch", lib.netfuse_time_next_launch(start_event, stop_event))
+
+
+def probe_mfma(sink, iters, stream=None):
+    """Launch the register-only matrix-instruction loop; returns the floating point operations it executes."""
+    fl = ctypes.c_double()
+    _check("netfuse_probe_mfma", lib.netfuse_probe_mfma(_ptr(sink), int(iters), ctypes.byref(fl), _stream(stream)))
+    return fl.value
+
+
+def probe_hbm_read(src, sink, stream=None):
+    """Launch the read-only stream over the whole of `src`; returns the bytes it reads."""
+    nbytes = src.numel() * src.element_size()
+    _check("netfuse_probe_hbm_read", lib.netfuse_probe_hbm_read(_ptr(src), nbytes, _ptr(sink), _stream(stream)))
+    return nbytes
 
 
 def conv_out_size(n, k, stride, pad, dil=1):

@@ -19,6 +19,7 @@
 #include "generic_kernels.h"
 #include "nf_common.h"
 #include "norm_kernels.h"
+#include "probe_kernels.h"
 
 using namespace nf;
 
@@ -210,6 +211,27 @@ nf_status netfuse_time_next_launch(void* start_event, void* stop_event) {
   t.start = (hipEvent_t)start_event;
   t.stop = (hipEvent_t)stop_event;
   return NF_OK;
+}
+
+nf_status netfuse_probe_mfma(void* sink, int iters, double* flops, void* stream) {
+  if (!sink || iters <= 0 || !flops) return NF_EINVAL;
+  if (!aligned(sink, 4)) return NF_EINVAL;
+  const int wgs = 256;                                        // one workgroup of 16 wavefronts per compute unit
+  *flops = (double)wgs * kProbeWaves * iters * 4 * kProbeFlopsPerMfma;
+  nf_launch(probe_mfma_kernel, dim3(wgs), dim3(kProbeWaves * kWave), 0, (hipStream_t)stream, (float*)sink, iters, 0);
+  return launched();
+}
+
+nf_status netfuse_probe_hbm_read(const void* src, long long bytes, void* sink, void* stream) {
+  if (!src || !sink || bytes < 16 || bytes % 16) return NF_EINVAL;
+  if (!aligned(src, 16) || !aligned(sink, 4)) return NF_EINVAL;
+  const size_t chunks = (size_t)bytes / 16;
+  const size_t per_wg = (size_t)256 * kProbeReadUnroll;
+  size_t wgs = (chunks + per_wg - 1) / per_wg;
+  if (wgs > 256 * 8) wgs = 256 * 8;                           // eight workgroups per compute unit, grid-stride beyond
+  nf_launch(probe_hbm_read_kernel, dim3((unsigned)wgs), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, chunks,
+            (uint32_t*)sink, 0);
+  return launched();
 }
 
 const char* netfuse_strerror(nf_status st) {
@@ -833,8 +855,17 @@ nf_status netfuse_merge_transpose(const void* src, void* dst, int M, int rows, i
   if (total >= kMaxElems) return NF_EINVAL;
   const size_t esz = dt == NF_F32 ? 4 : 2;
   if (!aligned(src, esz) || !aligned(dst, esz)) return NF_EINVAL;
-  const unsigned grid = grid_for(total, 256);
   hipStream_t s = (hipStream_t)stream;
+  // rows of H elements move as whole 16-byte vectors when they are made of them: the same index map over
+  // H * esz / 16 vectors per row
+  if (((size_t)H * esz) % 16 == 0 && aligned(src, 16) && aligned(dst, 16)) {
+    const int Hv = (int)((size_t)H * esz / 16);
+    const long long total_v = prod({M, rows, Hv});
+    nf_launch(merge_transpose_kernel<uint4>, dim3(grid_for(total_v, 256)), dim3(256), 0, s, (const uint4*)src, (uint4*)dst,
+              M, rows, Hv, to_channel != 0, (size_t)total_v);
+    return launched();
+  }
+  const unsigned grid = grid_for(total, 256);
   if (dt == NF_F32)
     nf_launch(merge_transpose_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)src, (float*)dst,
                        M, rows, H, to_channel != 0, (size_t)total);
