@@ -66,6 +66,8 @@ nf_status launch_gemm_frag(int cfg, GemmLaunch& L, hipStream_t s) {
     case F96: return launch_frag<FragCfg<3, 4, 1, NF_FRAG_NS>>(L, s);
     case F288: return launch_frag<FragCfg<9, 1, 2, NF_FRAG_NS>>(L, s);
     case F384: return launch_frag<FragCfg<12, 1, 2, NF_FRAG_NS>>(L, s);
+    case F128: return launch_frag<FragCfg<4, 1, 2, NF_FRAG_NS>>(L, s);
+    case F256: return launch_frag<FragCfg<8, 1, 2, NF_FRAG_NS>>(L, s);
   }
   return NF_EUNSUPPORTED;
 }

@@ -310,15 +310,20 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
 // ties go to the wider tile.  -1 if no tile fits.
 static int pick_frag(int N, int Nout, int K, int M) {
   if (N % 128 != 0) return -1;
-  int best = -1;
-  long long best_cost = 0;
-  for (int t = 0; t < kNumFragTiles; ++t) {
-    if (Nout % kFragBN[t] || K % kFragKUnit[t]) continue;
-    const long long tiles = (long long)M * (N / 128) * (Nout / kFragBN[t]);
-    const long long cost = (tiles + 255) / 256 * kFragBN[t];
-    if (best < 0 || cost < best_cost || (cost == best_cost && kFragBN[t] > kFragBN[best])) { best = t; best_cost = cost; }
-  }
-  return best;
+  auto best_of = [&](int lo, int hi) {
+    int best = -1;
+    long long best_cost = 0;
+    for (int t = lo; t < hi; ++t) {
+      if (Nout % kFragBN[t] || K % kFragKUnit[t]) continue;
+      const long long tiles = (long long)M * (N / 128) * (Nout / kFragBN[t]);
+      const long long cost = (tiles + 255) / 256 * kFragBN[t];
+      if (best < 0 || cost < best_cost || (cost == best_cost && kFragBN[t] > kFragBN[best])) { best = t; best_cost = cost; }
+    }
+    return best;
+  };
+  // the 12- and 9-wavefront tiles wherever one of them divides the width, else the 128 / 256 column ones
+  const int main_tile = best_of(0, kNumFragMainTiles);
+  return main_tile >= 0 ? main_tile : best_of(kNumFragMainTiles, kNumFragTiles);
 }
 
 // The 256 x 256 streaming kernel on packed weights (several column tiles per workgroup through one pipeline;

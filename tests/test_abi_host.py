@@ -80,11 +80,11 @@ def test_packed_linear_rejects_bad_arguments(lib):
     assert call(dt=0) == 2
     assert call(N=100) == 2                                             # not whole tiles: NF_EUNSUPPORTED
     assert call(K=64) == 2                                              # shorter than one round of the pipeline
-    assert call(Nout=128) == 2                                          # no tile width divides it
+    assert call(Nout=160) == 2                                          # no tile width divides it
     # the query agrees with what the call accepts
     assert can(32, 128, 768, 3072, 1) == 1 and can(32, 128, 3072, 768, 1) == 1 and can(64, 256, 128, 288, 1) == 1
     assert can(32, 128, 768, 3072, 0) == 0 and can(32, 100, 768, 3072, 1) == 0 and can(0, 128, 768, 768, 1) == 0
-    assert can(2, 128, 64, 96, 1) == 0 and can(2, 128, 256, 128, 1) == 0
+    assert can(2, 128, 64, 96, 1) == 0 and can(2, 128, 256, 160, 1) == 0 and can(128, 128, 256, 128, 1) == 1
     assert can(2, 256, 128, 288, 1) == 0 and can(8, 128, 3072, 768, 1) == 0      # a kernel exists, but too few tiles for it to pay
     assert can(2, 256, 64, 512, 1) == 1 and can(2, 256, 48, 512, 1) == 0    # 256 x 256 tiles: K in steps of 32
 

@@ -49,6 +49,10 @@ PACKED_CASES = [
     (2, 256, 64, 512, True, True, 1),         # only this kernel fits 512 columns; K shorter than the pipeline
     (3, 256, 96, 1024, False, True, 2),
     (1, 768, 160, 256, True, False, 0),       # three row tiles of one model
+    # widths that only the 128- and 256-column fragment tiles divide (a BERT-large-shaped layer)
+    (16, 128, 1024, 1024, True, True, 0),
+    (8, 128, 1024, 4096, True, False, 2),
+    (3, 128, 256, 640, False, True, 1),       # five tiles of 128
 ]
 
 
