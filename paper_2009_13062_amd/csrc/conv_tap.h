@@ -83,6 +83,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
   const bf16_t* xg = a.x + (long)b * a.x_image + (long)G * a.x_group;
   const bf16_t* wg = a.w + ((long)G * a.cog + row0) * a.cig * 9;
 
+  // ---- this thread's share of a channel block.  Weight task = (row, channel octet); patch task = (channel
+  // octet, patch row, chunk of VW pixels).  The geometry does not change from block to block.
+  int w_off[Cfg::kWPer], w_dst[Cfg::kWPer];                 // w_dst < 0: no such task
+#pragma unroll
+  for (int t = 0; t < Cfg::kWPer; ++t) {
+    const int task = tid + t * 256, r = task / (CB / 8), o = task % (CB / 8);
+    const bool live = Cfg::kWTasks % 256 == 0 || task < Cfg::kWTasks;
+    w_off[t] = (min(r, rows_left - 1) * a.cig + 8 * o) * 9;  // rows past the end re-read the last one; never stored
+    w_dst[t] = live ? r * Cfg::kAPitch + 8 * o : -1;
+  }
+  // ---- software pipeline over channel blocks: the global loads of block s+1 are in flight in registers
+  // while block s is multiplied out of LDS
+  uint32_t wv[Cfg::kWPer][36];
+  uint32_t pv[NT][8][kDw];
+  const long plane = (long)a.H * a.W;
+  auto prefetch_w = [&](int ci0) {
+#pragma unroll
+    for (int t = 0; t < Cfg::kWPer; ++t) {
+      if (FUSED || w_dst[t] < 0) continue;
+      const bf16_t* p = wg + w_off[t] + (long)ci0 * 9;
+#pragma unroll
+      for (int q = 0; q < 9; ++q) {
+        const uint4 v = *reinterpret_cast<const uint4*>(p + q * 8);
+        wv[t][4 * q] = v.x; wv[t][4 * q + 1] = v.y; wv[t][4 * q + 2] = v.z; wv[t][4 * q + 3] = v.w;
+      }
+    }
+  };
+  // The first block's weights are requested before anything else: the index arithmetic below (a handful of
+  // integer divisions per lane) and the zero fill of the patch then run under their trip from HBM instead of in
+  // front of it (measured: 2.8 us from the start of a workgroup to its first load otherwise).
+  prefetch_w(0);
+
+
   // ---- fragment addresses (elements): per-lane base + wave-uniform (tap, channel group) offset
   int b_off[FN];
 #pragma unroll
@@ -101,16 +134,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // ---- this thread's share of a channel block.  Weight task = (row, channel octet); patch task = (channel
-  // octet, patch row, chunk of VW pixels).  The geometry does not change from block to block.
-  int w_off[Cfg::kWPer], w_dst[Cfg::kWPer];                 // w_dst < 0: no such task
-#pragma unroll
-  for (int t = 0; t < Cfg::kWPer; ++t) {
-    const int task = tid + t * 256, r = task / (CB / 8), o = task % (CB / 8);
-    const bool live = Cfg::kWTasks % 256 == 0 || task < Cfg::kWTasks;
-    w_off[t] = (min(r, rows_left - 1) * a.cig + 8 * o) * 9;  // rows past the end re-read the last one; never stored
-    w_dst[t] = live ? r * Cfg::kAPitch + 8 * o : -1;
-  }
   int g_off[NT], l_off[NT];                                 // g_off < 0: nothing to copy
   {
     const int ntasks = (CB / 8) * PH * a.cpr;
@@ -128,22 +151,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
   // zero the whole patch once: padding and out-of-image rows are never written again
   for (int c = tid; c < a.PS * PP / 8; c += 256) lds_store16(Ps + c * 8, make_uint4(0, 0, 0, 0));
 
-  // ---- software pipeline over channel blocks: the global loads of block s+1 are in flight in registers
-  // while block s is multiplied out of LDS
-  uint32_t wv[Cfg::kWPer][36];
-  uint32_t pv[NT][8][kDw];
-  const long plane = (long)a.H * a.W;
-  auto prefetch = [&](int ci0) {
-#pragma unroll
-    for (int t = 0; t < Cfg::kWPer; ++t) {
-      if (FUSED || w_dst[t] < 0) continue;
-      const bf16_t* p = wg + w_off[t] + (long)ci0 * 9;
-#pragma unroll
-      for (int q = 0; q < 9; ++q) {
-        const uint4 v = *reinterpret_cast<const uint4*>(p + q * 8);
-        wv[t][4 * q] = v.x; wv[t][4 * q + 1] = v.y; wv[t][4 * q + 2] = v.z; wv[t][4 * q + 3] = v.w;
-      }
-    }
+  auto prefetch_x = [&](int ci0) {
     const bf16_t* xc = xg + (long)ci0 * plane;
 #pragma unroll
     for (int u = 0; u < NT; ++u) {
@@ -164,6 +172,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
         }
       }
     }
+  };
+  auto prefetch = [&](int ci0) {
+    prefetch_w(ci0);
+    prefetch_x(ci0);
   };
   // selectors of perm(hi, lo, sel): 16 bits of `lo` (its low or high half) below 16 bits of `hi`
   auto pick = [](int lo_half, int hi_half) -> uint32_t {
@@ -198,7 +210,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Cfg::kMinWa
     }
   };
 
-  prefetch(0);
+  prefetch_x(0);
   if constexpr (FUSED) {
     for (int c = tid; c < Cfg::kBM * Cfg::kAPitch / 8; c += 256) lds_store16(As + c * 8, make_uint4(0, 0, 0, 0));
     __syncthreads();
