@@ -602,6 +602,10 @@ struct TileCfg {
   static constexpr int kLdsBytes = kLdsPipe > kLdsEpi ? kLdsPipe : kLdsEpi;
 };
 
+#ifndef NF_REG_EPILOGUE
+#define NF_REG_EPILOGUE 1
+#endif
+
 template <int ACT>
 __device__ __forceinline__ float act_const(float v) {
   if constexpr (ACT == NF_ACT_RELU) return v > 0.f ? v : (v != v ? v : 0.f);
@@ -794,6 +798,80 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
   }
 }
 
+// The same epilogue straight from the accumulators, for outputs whose rows are 16-byte aligned and whole
+// 8-column pieces (ep.vec_store == 2) and that carry no per-column constants (every convolution): no staging
+// through LDS and no workgroup barrier.  A lane holds, per 32 x 32 block, four groups of 4 consecutive columns
+// of its row (columns 8 q + 4 half + 0..3); the two lanes of a row (lane, lane + 32) swap one group per pair of
+// groups so that each ends up with 8 consecutive columns: residual and output then move 16 bytes per lane.
+// Same arithmetic in the same order as the staged form, element by element: the two give the same bits.
+template <class Cfg, int ACT1, int ACT2>
+__device__ __forceinline__ void gemm_epilogue_regs(f32x16_t (&acc)[Cfg::FM][Cfg::FN], bf16_t* C, const bf16_t* R,
+                                                   long ldc, int rows_left, int cols_left, const Epilogue& ep,
+                                                   long row_vec_off) {
+  constexpr int FM = Cfg::FM, FN = Cfg::FN;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int wm = wave / Cfg::kWGN, wn = wave % Cfg::kWGN;
+  const int half = lane / 32, l32 = lane % 32;
+  float rbs[FM], rss[FM], rts[FM];
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    rbs[i] = 0.f; rss[i] = 1.f; rts[i] = 0.f;
+    const int row = wm * Cfg::WM + i * 32 + l32;
+    if (row < rows_left) {
+      if (ep.row_bias) rbs[i] = ep.row_bias[row_vec_off + row];
+      if (ep.row_scale) { rss[i] = ep.row_scale[row_vec_off + row]; rts[i] = ep.row_shift[row_vec_off + row]; }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int row = wm * Cfg::WM + i * 32 + l32;
+    const bool row_ok = row < rows_left;
+    // this lane's pieces: columns colb + 16 qq + 8 half + 0..7
+    uint4 rr[FN][2];
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int qq = 0; qq < 2; ++qq) {
+        const int col = wn * Cfg::WN + j * 32 + 16 * qq + 8 * half;
+        rr[j][qq] = (R != nullptr && row_ok && col < cols_left) ? *reinterpret_cast<const uint4*>(R + (long)row * ldc + col)
+                                                                : make_uint4(0u, 0u, 0u, 0u);
+      }
+#pragma unroll
+    for (int j = 0; j < FN; ++j)
+#pragma unroll
+      for (int qq = 0; qq < 2; ++qq) {
+        float own[4], send[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          // group 2 qq + half stays (its other half comes from the partner), group 2 qq + 1 - half is sent
+          const float v0 = act_const<ACT1>(fmaf(acc[i][j][(2 * qq) * 4 + e] + 0.f + rbs[i], rss[i], rts[i]));
+          const float v1 = act_const<ACT1>(fmaf(acc[i][j][(2 * qq + 1) * 4 + e] + 0.f + rbs[i], rss[i], rts[i]));
+          own[e] = half ? v1 : v0;
+          send[e] = half ? v0 : v1;
+        }
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float recv = __shfl_xor(send[e], 32, kWave);
+          v[e] = half ? recv : own[e];
+          v[4 + e] = half ? own[e] : recv;
+        }
+        const int col = wn * Cfg::WN + j * 32 + 16 * qq + 8 * half;
+        if (row_ok && col < cols_left) {
+          const uint32_t w[4] = {rr[j][qq].x, rr[j][qq].y, rr[j][qq].z, rr[j][qq].w};
+          uint32_t o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float a0 = act_const<ACT2>(v[2 * e] + __uint_as_float(w[e] << 16));
+            const float a1 = act_const<ACT2>(v[2 * e + 1] + __uint_as_float(w[e] & 0xffff0000u));
+            o[e] = pack_bf16x2(a0, a1);
+          }
+          *reinterpret_cast<uint4*>(C + (long)row * ldc + col) = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+      }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // Epilogue shared by the contraction kernels.  acc[i][j] holds rows wm*WM + 32 i .. and columns
 // wn*WN + 32 j .. of the tile, transposed: register r of lane l is row (l % 32), column
@@ -808,7 +886,9 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[Cfg::FM][Cfg::FN],
                                               const Epilogue& ep, long row_vec_off, long col_vec_off) {
 #define NF_EPI(A1, A2)                                                                                          \
   do {                                                                                                          \
-    if (ep.vec_store == 1 || ep.vec_store == 3)                                                                 \
+    if (NF_REG_EPILOGUE && Cfg::kRowConsts && ep.vec_store == 2 && ep.col_bias == nullptr)                       \
+      gemm_epilogue_regs<Cfg, A1, A2>(acc, C, R, ldc, rows_left, cols_left, ep, row_vec_off);                   \
+    else if (ep.vec_store == 1 || ep.vec_store == 3)                                                                 \
       gemm_epilogue_act<Cfg, A1, A2, true>(acc, Es, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off); \
     else                                                                                                        \
       gemm_epilogue_act<Cfg, A1, A2, false>(acc, Es, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off); \
