@@ -822,20 +822,24 @@ __device__ __forceinline__ void gemm_epilogue_regs(f32x16_t (&acc)[Cfg::FM][Cfg:
       if (ep.row_scale) { rss[i] = ep.row_scale[row_vec_off + row]; rts[i] = ep.row_shift[row_vec_off + row]; }
     }
   }
+  // this lane's residual pieces (columns colb + 16 qq + 8 half + 0..7 of its FM rows), all requested together
+  uint4 rr[FM][FN][2];
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
     const int row = wm * Cfg::WM + i * 32 + l32;
-    const bool row_ok = row < rows_left;
-    // this lane's pieces: columns colb + 16 qq + 8 half + 0..7
-    uint4 rr[FN][2];
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int qq = 0; qq < 2; ++qq) {
         const int col = wn * Cfg::WN + j * 32 + 16 * qq + 8 * half;
-        rr[j][qq] = (R != nullptr && row_ok && col < cols_left) ? *reinterpret_cast<const uint4*>(R + (long)row * ldc + col)
-                                                                : make_uint4(0u, 0u, 0u, 0u);
+        rr[i][j][qq] = (R != nullptr && row < rows_left && col < cols_left)
+                           ? *reinterpret_cast<const uint4*>(R + (long)row * ldc + col) : make_uint4(0u, 0u, 0u, 0u);
       }
+  }
+#pragma unroll
+  for (int i = 0; i < FM; ++i) {
+    const int row = wm * Cfg::WM + i * 32 + l32;
+    const bool row_ok = row < rows_left;
 #pragma unroll
     for (int j = 0; j < FN; ++j)
 #pragma unroll
@@ -858,7 +862,7 @@ __device__ __forceinline__ void gemm_epilogue_regs(f32x16_t (&acc)[Cfg::FM][Cfg:
         }
         const int col = wn * Cfg::WN + j * 32 + 16 * qq + 8 * half;
         if (row_ok && col < cols_left) {
-          const uint32_t w[4] = {rr[j][qq].x, rr[j][qq].y, rr[j][qq].z, rr[j][qq].w};
+          const uint32_t w[4] = {rr[i][j][qq].x, rr[i][j][qq].y, rr[i][j][qq].z, rr[i][j][qq].w};
           uint32_t o[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
