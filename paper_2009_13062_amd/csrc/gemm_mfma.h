@@ -804,7 +804,9 @@ __device__ __forceinline__ void gemm_epilogue_act(f32x16_t (&acc)[Cfg::FM][Cfg::
 // of its row (columns 8 q + 4 half + 0..3); the two lanes of a row (lane, lane + 32) swap one group per pair of
 // groups so that each ends up with 8 consecutive columns: residual and output then move 16 bytes per lane.
 // Same arithmetic in the same order as the staged form, element by element: the two give the same bits.
-template <class Cfg, int ACT1, int ACT2>
+// TAIL4 (ep.vec_store == 1: rows 8-byte aligned, widths multiples of 4, e.g. 14 x 14 planes): the 16-byte accesses
+// then sit on 8-byte boundaries, and the last piece of a row may be its first 4 columns only (8 bytes).
+template <class Cfg, int ACT1, int ACT2, bool TAIL4 = false>
 __device__ __forceinline__ void gemm_epilogue_regs(f32x16_t (&acc)[Cfg::FM][Cfg::FN], bf16_t* C, const bf16_t* R,
                                                    long ldc, int rows_left, int cols_left, const Epilogue& ep,
                                                    long row_vec_off) {
@@ -832,8 +834,15 @@ __device__ __forceinline__ void gemm_epilogue_regs(f32x16_t (&acc)[Cfg::FM][Cfg:
 #pragma unroll
       for (int qq = 0; qq < 2; ++qq) {
         const int col = wn * Cfg::WN + j * 32 + 16 * qq + 8 * half;
-        rr[i][j][qq] = (R != nullptr && row < rows_left && col < cols_left)
-                           ? *reinterpret_cast<const uint4*>(R + (long)row * ldc + col) : make_uint4(0u, 0u, 0u, 0u);
+        rr[i][j][qq] = make_uint4(0u, 0u, 0u, 0u);
+        if (R != nullptr && row < rows_left && col < cols_left) {
+          if (!TAIL4 || col + 8 <= cols_left) {
+            rr[i][j][qq] = *reinterpret_cast<const uint4*>(R + (long)row * ldc + col);
+          } else {
+            const uint2 lo = *reinterpret_cast<const uint2*>(R + (long)row * ldc + col);
+            rr[i][j][qq] = make_uint4(lo.x, lo.y, 0u, 0u);
+          }
+        }
       }
   }
 #pragma unroll
@@ -870,7 +879,8 @@ __device__ __forceinline__ void gemm_epilogue_regs(f32x16_t (&acc)[Cfg::FM][Cfg:
             const float a1 = act_const<ACT2>(v[2 * e + 1] + __uint_as_float(w[e] & 0xffff0000u));
             o[e] = pack_bf16x2(a0, a1);
           }
-          *reinterpret_cast<uint4*>(C + (long)row * ldc + col) = make_uint4(o[0], o[1], o[2], o[3]);
+          if (!TAIL4 || col + 8 <= cols_left) *reinterpret_cast<uint4*>(C + (long)row * ldc + col) = make_uint4(o[0], o[1], o[2], o[3]);
+          else *reinterpret_cast<uint2*>(C + (long)row * ldc + col) = make_uint2(o[0], o[1]);
         }
       }
   }
@@ -892,6 +902,8 @@ __device__ __forceinline__ void gemm_epilogue(f32x16_t (&acc)[Cfg::FM][Cfg::FN],
   do {                                                                                                          \
     if (NF_REG_EPILOGUE && Cfg::kRowConsts && ep.vec_store == 2 && ep.col_bias == nullptr)                       \
       gemm_epilogue_regs<Cfg, A1, A2>(acc, C, R, ldc, rows_left, cols_left, ep, row_vec_off);                   \
+    else if (NF_REG_EPILOGUE && Cfg::kRowConsts && ep.vec_store == 1 && ep.col_bias == nullptr)                  \
+      gemm_epilogue_regs<Cfg, A1, A2, true>(acc, C, R, ldc, rows_left, cols_left, ep, row_vec_off);             \
     else if (ep.vec_store == 1 || ep.vec_store == 3)                                                                 \
       gemm_epilogue_act<Cfg, A1, A2, true>(acc, Es, C, R, ldc, rows_left, cols_left, ep, row_vec_off, col_vec_off); \
     else                                                                                                        \
