@@ -502,7 +502,14 @@ def test_graph_replay_equals_eager_forward(nf):
     spec = NI.resnet_spec(cardinality=8, base_width=8, image=64, width_div=2, depths=(1, 1, 1, 1))
     rinp = NI.resnet_params(spec, M, bf16=True)
     net = ResNetForward.from_numpy(rinp, spec, M)
-    for fwd, x0 in ((enc.forward, dev(inp["X"], torch.bfloat16)), (net.forward, dev(rinp["x"], torch.bfloat16))):
+    # and the configuration bench.py times: packed weights, 32 models, one full-size layer
+    from netfuse_inputs.device import encoder_stack_device
+    pshape = NI.EncoderShape(layers=1, seq=128)
+    pinp = encoder_stack_device(32, pshape, cfg=5)
+    penc = EncoderStack(pinp["layers"], 32, 1, pshape.seq, pshape.heads, packed=True)
+    assert all(k + "_p" in penc.layers[0] for k in ("Wqkv", "Wo", "W1", "W2"))
+    for fwd, x0 in ((enc.forward, dev(inp["X"], torch.bfloat16)), (net.forward, dev(rinp["x"], torch.bfloat16)),
+                    (penc.forward, pinp["X"])):
         x = x0.clone()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
