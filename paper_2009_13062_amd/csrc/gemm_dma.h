@@ -98,6 +98,9 @@ __device__ __forceinline__ void wait_lgkmcnt0() {
 // Only launches whose workgroups are all resident at once (one per compute unit) and whose A operands fit
 // the L2 of an XCD beside the weight stream do this: 512 x 3072 activations per model (four models per XCD:
 // 12 MB against 4 MB of L2) measured 10 % slower with it, as did launches of several rounds of workgroups.
+// At 3 MB per XCD (128 x 3072 per model, the 3072 -> 768 matmul) it still pays, if less: 41.2 -> 39.0 us behind
+// the matmul that wrote the operand (34 us on a never rewritten one: part of the lines is evicted by the
+// weight stream before its use).
 #ifndef NF_A_TOUCH
 #define NF_A_TOUCH 1
 #endif
@@ -106,7 +109,7 @@ __device__ __forceinline__ void wait_lgkmcnt0() {
 // in-order memory queue in front of its own pipeline stages.)
 inline bool touch_a_pays(long long workgroups, long long a_elems_per_problem, long long problems) {
   const long long per_xcd = (problems + kNumXcd - 1) / kNumXcd * a_elems_per_problem * 2;      // bytes
-  return workgroups <= 256 && per_xcd <= (1 << 20);
+  return workgroups <= 256 && per_xcd <= (3 << 20);
 }
 template <class Cfg>
 __device__ __forceinline__ void touch_a_rows(const bf16_t* A, long lda, int K, int part, int parts) {
