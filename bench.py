@@ -207,11 +207,12 @@ def roofline_for(agg):
 
 
 # ------------------------------------------------------------------------------------------
+CONCURRENT_STREAMS = 4    # streams of the Concurrent stand-in (the box exposes 4 hardware queues per process)
 PACKED_WEIGHTS = True     # encoder matmuls on weights packed once by netfuse_linear_pack_weight (--unpacked: off)
 
 
 def build_workload(name, torch, M=None, batch=1):
-    """-> (forward(), [per-model forward()], config, M, inferences per step)."""
+    """-> (merged forward(), all models one after the other(), config, M, inferences per step, [model m alone()])."""
     import netfuse_inputs as NI
     from netfuse_inputs.device import encoder_stack_device, resnet_params_device
     from paper_2009_13062_amd.workloads import EncoderStack, ResNetForward
@@ -239,7 +240,13 @@ def build_workload(name, torch, M=None, batch=1):
             for pm in per:
                 for m, one in enumerate(pm):
                     one.forward(x[m:m + 1])
-        return merged, separate, cfg, M, rot
+
+        def alone(m):
+            def run():
+                for pm in per:
+                    pm[m].forward(x[m:m + 1])
+            return run
+        return merged, separate, cfg, M, rot, [alone(m) for m in range(M)]
     spec = NI.resnet_spec(cardinality=p["card"], base_width=p["bw"])
     inp = resnet_params_device(spec, M, cfg=p["cfg"], batch=batch)
     net = ResNetForward(spec, inp["params"], M, batch=batch)
@@ -251,7 +258,7 @@ def build_workload(name, torch, M=None, batch=1):
     def separate():
         for one, xm in singles:
             one.forward(xm)
-    return (lambda: net.forward(x)), separate, cfg, M, 1
+    return (lambda: net.forward(x)), separate, cfg, M, 1, [(lambda one=one, xm=xm: one.forward(xm)) for one, xm in singles]
 
 
 def timed(torch, fn, steps, warmup):
@@ -271,6 +278,24 @@ def timed(torch, fn, steps, warmup):
     wall = (time.perf_counter() - t0) * 1e3 / steps
     per = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
     return wall, (statistics.pstdev(per) if steps > 1 else 0.0), statistics.mean(per)
+
+
+def concurrent_streams(torch, singles, nstreams):
+    """The models dealt over `nstreams` streams of the default priority, each model's launches in order on its
+    stream: a single-process stand-in for the paper's Concurrent baseline (Section 5.1: one process per model
+    on the same GPU).  Fork from and join into the current stream."""
+    streams = [torch.cuda.Stream() for _ in range(nstreams)]
+
+    def run():
+        cur = torch.cuda.current_stream()
+        for st in streams:
+            st.wait_stream(cur)
+        for i, f in enumerate(singles):
+            with torch.cuda.stream(streams[i % nstreams]):
+                f()
+        for st in streams:
+            cur.wait_stream(st)
+    return run
 
 
 def make_graph(torch, fn):
@@ -337,8 +362,8 @@ def kernel_pass(torch, nf, events, fn, npass):
 
 
 def run_workload(name, steps, warmup, use_graph, torch, nf, events, separate_too=True, M=None, batch=1,
-                 sep_steps=None, kernels=True):
-    merged, separate, cfg, M, per_step = build_workload(name, torch, M=M, batch=batch)
+                 sep_steps=None, kernels=True, concurrent=0):
+    merged, separate, cfg, M, per_step, singles = build_workload(name, torch, M=M, batch=batch)
     res = dict(config=cfg)
     best, sd = best_of(torch, merged, steps, warmup, use_graph, res, "")
     res["ms_per_step"] = best / per_step
@@ -352,6 +377,15 @@ def run_workload(name, steps, warmup, use_graph, torch, nf, events, separate_too
         res["speedup_vs_separate"] = sbest / best
     else:
         res["separate_ms"] = res["separate_inferences_per_s"] = res["speedup_vs_separate"] = None
+    if concurrent and separate_too:
+        ss = sep_steps or steps
+        cres = {}
+        cw, csd = best_of(torch, concurrent_streams(torch, singles, concurrent), ss, max(1, warmup // 2), use_graph, cres, "")
+        res["concurrent"] = dict(streams=concurrent, ms_per_step=cw / per_step, ms_per_step_std=csd / per_step,
+                                 inferences_per_s=M * batch / (cw / per_step * 1e-3), steps=ss,
+                                 speedup_vs_concurrent=cw / best, **cres,
+                                 note="the M single-model forwards dealt over this many streams of one process; "
+                                      "eager launches are bound by the host's launch rate, the captured graph is not")
     if kernels:
         npass = max(3, min(steps, 10))
         agg = kernel_pass(torch, nf, events, merged, npass)
@@ -552,7 +586,12 @@ def main():
     sweep_steps = max(5, min(args.steps, 30))
     t_start = time.time()
     head = run_workload(args.workload, args.steps, args.warmup, use_graph, torch, nf, events,
-                        separate_too=not args.no_separate, sep_steps=sweep_steps)
+                        separate_too=not args.no_separate, sep_steps=sweep_steps,
+                        concurrent=0 if args.quick else CONCURRENT_STREAMS)
+    if head.get("concurrent"):
+        log("[bench] %s: the models on %d streams %.3f ms/step (%.2fx)" % (
+            args.workload, head["concurrent"]["streams"], head["concurrent"]["ms_per_step"],
+            head["concurrent"]["speedup_vs_concurrent"]))
     log("[bench] %s: %.3f +- %.3f ms/step, %.1f inf/s, %sx vs separate (%.1f s)" % (
         args.workload, head["ms_per_step"], head["ms_per_step_std"], head["inferences_per_s"],
         "%.2f" % head["speedup_vs_separate"] if head["speedup_vs_separate"] else "-", time.time() - t_start))
@@ -609,6 +648,7 @@ def main():
         "separate_launches": {"ms_per_step": head["separate_ms"], "inferences_per_s": head["separate_inferences_per_s"],
                               "steps": sweep_steps},
         "speedup_vs_separate": head["speedup_vs_separate"],
+        "concurrent_streams": head.get("concurrent"),
         "launch": {k: head[k] for k in ("eager_ms", "graph_ms", "separate_eager_ms", "separate_graph_ms", "graph_error") if k in head},
         "model_TFLOPs": head["model_TFLOPs"],
         "kernel_time_ms_per_step": head["kernel_time_ms_per_step"],
