@@ -541,8 +541,8 @@ def cpu_baseline(name):
     threads = int(os.environ.get("OMP_NUM_THREADS", cores))
     oracle.build()
     if kind == "encoder":
-        # about 10 s including input generation: every model through 1 layer (seq 128), 4 models through 1 layer (seq 512)
-        ms, nl = (min(M, 32), 1) if p["seq"] <= 128 else (min(M, 4), 1)
+        # about 10 s of oracle time: every model through 3 layers (seq 128), 8 models through 1 layer (seq 512)
+        ms, nl = (min(M, 32), min(3, p["layers"])) if p["seq"] <= 128 else (min(M, 8), 1)
         shape = NI.EncoderShape(layers=nl, seq=p["seq"])
         inp = NI.encoder_stack(ms, shape, cfg=p["cfg"], bf16=True)
         t0 = time.perf_counter()

@@ -9,6 +9,14 @@
  * operations without weights, DontCare = the majority of its parents), and gets a reshape-and-transpose
  * operation on every incoming edge whose dimension conflicts (Batch against Channel).  Time O(|V| + |E|).
  *
+ * Common backbones (Section 3.2, last paragraph; Section 6): networks that share a backbone but end in layers
+ * of their own -- the fully connected layers of different downstream tasks -- are merged up to those layers,
+ * which stay as they are.  Such a layer is described once, as NF_OP_TASK_HEAD (a fully connected layer whose
+ * output width differs from network to network, so it carries no width): netfuse_graph_merge does NOT merge it
+ * -- its K is unchanged -- but records that M instances of it follow, each reading its own network's rows of
+ * the backbone's output, i.e. the batch-concatenated form (a reshape is inserted if the backbone ends channel-
+ * concatenated).  It must be a leaf: nothing past the backbone is merged, so nothing past it is described.
+ *
  * Attribute slots per kind (netfuse_graph_add_op's attrs, and what netfuse_graph_get_op returns):
  *   NF_OP_MATMUL       { K, Nout, has_bias, batch }              batch: 1 in a single model, M after merging
  *   NF_OP_CONV2D       { Cin, Cout, k, stride, pad, groups, has_bias }   Cin, Cout, groups are multiplied by M
@@ -17,8 +25,9 @@
  *   NF_OP_ATTENTION    { heads, d, batch }                       batch: 1 -> M
  *   NF_OP_MAXPOOL      { k, stride, pad }
  *   NF_OP_RESHAPE_TRANSPOSE { from_dim, to_dim }                 merged graphs only
+ *   NF_OP_TASK_HEAD    { K, has_bias, instances }                instances: 1 -> M (M unmerged layers)
  *   others             none
- * Trailing slots that are not passed default to 1 for batch / groups and to 0 otherwise.
+ * Trailing slots that are not passed default to 1 for batch / groups / instances and to 0 otherwise.
  *
  * Readings where the printed algorithm is silent: an operation is processed once all its parents are
  * (one reached early through a short branch waits); DontCare is compatible with both definite
@@ -40,7 +49,7 @@ typedef struct nf_graph nf_graph;
 typedef enum {
   NF_OP_INPUT = 0, NF_OP_MATMUL = 1, NF_OP_CONV2D = 2, NF_OP_LAYERNORM = 3, NF_OP_BATCHNORM = 4,
   NF_OP_ATTENTION = 5, NF_OP_RELU = 6, NF_OP_GELU = 7, NF_OP_ADD = 8, NF_OP_MAXPOOL = 9,
-  NF_OP_AVGPOOL_GLOBAL = 10, NF_OP_RESHAPE_TRANSPOSE = 11
+  NF_OP_AVGPOOL_GLOBAL = 10, NF_OP_RESHAPE_TRANSPOSE = 11, NF_OP_TASK_HEAD = 12
 } nf_op_kind;
 
 /* d_i of Algorithm 1: the dimension along which the tensors of the M instances are concatenated */
@@ -57,7 +66,8 @@ int netfuse_graph_add_op(nf_graph* g, int kind, const int* parents, int n_parent
 int netfuse_graph_size(const nf_graph* g);
 
 /* Algorithm 1.  The result lists every merged operation in the order it was visited, each preceded by the
- * reshape operations inserted on its incoming edges, so parents always precede children. */
+ * reshape operations inserted on its incoming edges, so parents always precede children.  NULL for M <= 0, a
+ * graph with unreachable operations, or a task head that has a consumer. */
 nf_graph* netfuse_graph_merge(const nf_graph* common, int M);
 
 /* Reads operation `id`: kind, concatenation dimension (NF_DIM_DONTCARE in an un-merged graph), the id of the
@@ -76,13 +86,16 @@ int netfuse_graph_get_op(const nf_graph* g, int id, int* kind, int* concat_dim, 
  *   [reshape ->] layernorm [-> reshape]                     one netfuse_layernorm in the producer's layout
  *   attention, maxpool, avgpool_global                      one call each
  *   any other reshape                                       netfuse_merge_transpose
+ *   task head (M unmerged fully connected layers)           one netfuse_linear_ragged: the M layers in one
+ *                                                            launch, each with its own output width (the
+ *                                                            caller holds the widths and the weights)
  *   relu / gelu / add that could not be folded              NF_CALL_UNFUSED (the caller has no entry point for
  *                                                            them; none of the workloads produces one)
  * A producer is folded into only when the folded operation is its single consumer.
  */
 typedef enum {
   NF_CALL_LINEAR = 0, NF_CALL_CONV2D = 1, NF_CALL_LAYERNORM = 2, NF_CALL_ATTENTION = 3, NF_CALL_MAXPOOL = 4,
-  NF_CALL_AVGPOOL_GLOBAL = 5, NF_CALL_MERGE_TRANSPOSE = 6, NF_CALL_UNFUSED = 7
+  NF_CALL_AVGPOOL_GLOBAL = 5, NF_CALL_MERGE_TRANSPOSE = 6, NF_CALL_UNFUSED = 7, NF_CALL_LINEAR_RAGGED = 8
 } nf_call_kind;
 
 typedef struct {

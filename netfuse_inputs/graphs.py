@@ -6,7 +6,8 @@ subgraph down for the architectures of the workloads: a list of nodes, each a di
 (parents always precede children).  No merging logic lives here: the C++ merger of the library and the
 Python oracle both take these lists as their input.
 
-kinds: input, matmul, conv2d, layernorm, batchnorm, attention, relu, gelu, add, maxpool, avgpool_global
+kinds: input, matmul, conv2d, layernorm, batchnorm, attention, relu, gelu, add, maxpool, avgpool_global,
+task_head (a fully connected layer outside the common backbone: Section 3.2, last paragraph; Section 6)
 """
 from __future__ import annotations
 
@@ -58,6 +59,14 @@ def encoder_stack_graph(shape: EncoderShape) -> List[Node]:
     for L in range(shape.layers):
         x = encoder_layer(g, x, shape, "l%d." % L)
     return g.nodes
+
+
+def encoder_with_task_heads_graph(shape: EncoderShape) -> List[Node]:
+    """The encoder stack as the common backbone of networks fine-tuned for different tasks (Section 6): every
+    network ends in a fully connected layer of its own width on the backbone's output."""
+    nodes = encoder_stack_graph(shape)
+    nodes.append(dict(kind="task_head", parents=[len(nodes) - 1], attrs=dict(K=shape.hidden, bias=1), name="head"))
+    return nodes
 
 
 def resnet_graph(spec: ResNetSpec) -> List[Node]:

@@ -19,6 +19,10 @@ Readings of the paper recorded here (where the printed algorithm is silent):
     printed listing would otherwise copy an edge from a parent that has no merged operation yet.
   * Batch and Channel conflict with each other only; DontCare is compatible with both (the text after the
     listing names exactly these two conflicts), so the inputs of the network need no reshape.
+  * Common backbones (the paragraph after the listing): the layers a network does not share are not part of
+    (V, E); here the one kind the paper names -- the per-task fully connected layer -- may be written down as a
+    leaf "task_head" so that the merged graph says where the M unmerged layers attach and in which form they
+    read the backbone's output.
   * MostFrequent ignores parents that are themselves still DontCare, and on a tie takes the dimension
     of the first parent among the tied ones; with no parent of a definite dimension the operation
     stays DontCare.
@@ -53,6 +57,12 @@ def merge_op(node: Dict, M: int):
     if kind == "attention":
         a["batch"] = a.get("batch", 1) * M
         return a, BATCH
+    if kind == "task_head":
+        # Section 3.2, last paragraph / Section 6: only the common backbone is merged; a layer of a network's
+        # own (the fully connected layer of its downstream task) stays as it is -- M instances of it, each
+        # reading its own network's rows, which only the batch concatenation keeps together
+        a["instances"] = a.get("instances", 1) * M
+        return a, BATCH
     if kind in ("input", "relu", "gelu", "add", "maxpool", "avgpool_global"):
         return a, DONTCARE
     raise ValueError("no merge rule for operation kind %r" % kind)
@@ -73,6 +83,8 @@ def merge_graph(nodes: List[Dict], M: int) -> List[Dict]:
     children: List[List[int]] = [[] for _ in range(n)]
     for i, nd in enumerate(nodes):
         for p in nd["parents"]:
+            if nodes[p]["kind"] == "task_head":
+                raise ValueError("a task head lies outside the common backbone: nothing after it is merged")
             children[p].append(i)
     merged: List[Dict] = []
     m_of: List[Optional[int]] = [None] * n          # index of m_i in the merged list

@@ -22,7 +22,7 @@ struct Op {
   long attrs[NF_GRAPH_MAX_ATTRS];
 };
 
-bool valid_kind(int k) { return k >= NF_OP_INPUT && k <= NF_OP_RESHAPE_TRANSPOSE; }
+bool valid_kind(int k) { return k >= NF_OP_INPUT && k <= NF_OP_TASK_HEAD; }
 
 // slot of the "how many independent weight sets" attribute, or -1
 int count_slot(int kind) {
@@ -30,6 +30,7 @@ int count_slot(int kind) {
     case NF_OP_MATMUL: return 3;
     case NF_OP_LAYERNORM: return 1;
     case NF_OP_ATTENTION: return 2;
+    case NF_OP_TASK_HEAD: return 2;
   }
   return -1;
 }
@@ -44,6 +45,9 @@ int merge_op(Op& m, int M) {
     case NF_OP_LAYERNORM: m.attrs[1] *= M; return NF_DIM_CHANNEL;        // group normalisation with M groups
     case NF_OP_BATCHNORM: m.attrs[0] *= M; return NF_DIM_CHANNEL;        // per channel: concatenated channels
     case NF_OP_ATTENTION: m.attrs[2] *= M; return NF_DIM_BATCH;          // M times the independent problems
+    // outside the common backbone (Section 3.2, last paragraph): not merged -- M instances of the layer as it
+    // is, each on its own network's rows, which are contiguous in the batch-concatenated form
+    case NF_OP_TASK_HEAD: m.attrs[2] *= M; return NF_DIM_BATCH;
     default: return NF_DIM_DONTCARE;                                     // no weights
   }
 }
@@ -106,7 +110,10 @@ nf_graph* netfuse_graph_merge(const nf_graph* common, int M) {
   const int n = (int)V.size();
   std::vector<std::vector<int>> children(n);
   for (int i = 0; i < n; ++i)
-    for (int p : V[i].parents) children[p].push_back(i);
+    for (int p : V[i].parents) {
+      if (V[p].kind == NF_OP_TASK_HEAD) return nullptr;   // nothing past the backbone is merged or described
+      children[p].push_back(i);
+    }
 
   nf_graph* out = new (std::nothrow) nf_graph();
   if (!out) return nullptr;
@@ -251,6 +258,7 @@ int netfuse_graph_lower(const nf_graph* merged, nf_call* calls, int cap) {
         }
         break;
       }
+      case NF_OP_TASK_HEAD: c.call = NF_CALL_LINEAR_RAGGED; break;
       case NF_OP_ATTENTION: c.call = NF_CALL_ATTENTION; break;
       case NF_OP_MAXPOOL: c.call = NF_CALL_MAXPOOL; break;
       case NF_OP_AVGPOOL_GLOBAL: c.call = NF_CALL_AVGPOOL_GLOBAL; break;

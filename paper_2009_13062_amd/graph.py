@@ -13,9 +13,10 @@ from typing import Dict, List, Sequence
 from . import lib as _lib
 
 KINDS = ("input", "matmul", "conv2d", "layernorm", "batchnorm", "attention", "relu", "gelu", "add", "maxpool",
-         "avgpool_global", "reshape_transpose")
+         "avgpool_global", "reshape_transpose", "task_head")
 DIMS = ("Batch", "Channel", "DontCare")
-CALLS = ("linear", "conv2d", "layernorm", "attention", "maxpool2d", "avgpool_global", "merge_transpose", "unfused")
+CALLS = ("linear", "conv2d", "layernorm", "attention", "maxpool2d", "avgpool_global", "merge_transpose", "unfused",
+         "linear_ragged")
 # attribute slots per kind (include/netfuse_graph.h)
 SLOTS = {
     "matmul": ("K", "Nout", "bias", "batch"),
@@ -25,8 +26,9 @@ SLOTS = {
     "attention": ("heads", "d", "batch"),
     "maxpool": ("k", "stride", "pad"),
     "reshape_transpose": ("from", "to"),
+    "task_head": ("K", "bias", "instances"),
 }
-_DEFAULT_ONE = ("batch", "groups")
+_DEFAULT_ONE = ("batch", "groups", "instances")
 MAX_ATTRS = 8
 
 
@@ -110,7 +112,8 @@ class Graph:
 def run_calls(calls, merged_nodes, common_nodes, M, graph_input, weights, batch=1, seq=None, eps=1e-5):
     """Executes a lowered call list.  ``weights[name]`` holds the merged parameters of the operation of the
     common subgraph called ``name``: matmul {"W", "b"}, layernorm {"gamma", "beta"}, conv2d {"w"} and, for the
-    batch normalisation folded into it, {"scale", "shift"} under the batch norm's own name.
+    batch normalisation folded into it, {"scale", "shift"} under the batch norm's own name; a task head
+    {"W", "b", "nout"}: the M unmerged layers' weights and biases one after another and their output widths.
     Returns {merged operation id: output tensor}."""
     import paper_2009_13062_amd as nf
     T = {}
@@ -141,6 +144,9 @@ def run_calls(calls, merged_nodes, common_nodes, M, graph_input, weights, batch=
             y = nf.maxpool2d(x, a["k"], a["stride"], a["pad"])
         elif c["call"] == "avgpool_global":
             y = nf.avgpool_global(x)
+        elif c["call"] == "linear_ragged":
+            w = weights[name_of(c["op"])]
+            y = nf.linear_ragged(x, w["W"], w["nout"], bias=w.get("b"))
         elif c["call"] == "merge_transpose":
             y = nf.merge_transpose(x, M, bool(c["layout"]))
         else:

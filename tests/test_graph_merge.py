@@ -66,6 +66,31 @@ def test_oracle_waits_for_all_parents():
     assert m[4]["parents"] == [0, 3] and m[4]["dim"] == "Channel"
 
 
+def test_oracle_merges_the_common_backbone_only():
+    """Section 3.2 (paragraph after the listing) and Section 6: networks that share a backbone are merged up to
+    their own layers, which are left as they are.  Example: the two-layer network of Section 3.2 as the
+    backbone, then one fully connected layer per network."""
+    g = G.ffnn_example(K=16, Nout=16) + [node("task_head", [2], K=16, bias=1)]
+    m = OG.merge_graph(g, 5)
+    assert [n["kind"] for n in m] == ["input", "matmul", "reshape_transpose", "layernorm", "reshape_transpose", "task_head"]
+    head = m[-1]
+    # not merged: its own attributes are untouched (no batch matmul over a common width, K is not multiplied),
+    # it only records that there are M of it ...
+    assert head["attrs"] == {"K": 16, "bias": 1, "instances": 5} and head["source"] == 3
+    # ... and each reads its own network's rows: the batch form, so the channel-merged normalisation's output
+    # is reshaped back
+    assert head["dim"] == "Batch" and m[4]["attrs"] == {"from": "Channel", "to": "Batch"} and head["parents"] == [4]
+    # the backbone is merged exactly as without the heads
+    assert m[:4] == OG.merge_graph(G.ffnn_example(K=16, Nout=16), 5)
+    # a batch-merged backbone output needs no reshape; several heads on one backbone are all left alone
+    g2 = [node("input"), node("matmul", [0], K=8, Nout=8, bias=0), node("task_head", [1], K=8, bias=0), node("task_head", [1], K=8, bias=1)]
+    m2 = OG.merge_graph(g2, 3)
+    assert [n["kind"] for n in m2] == ["input", "matmul", "task_head", "task_head"] and m2[1]["attrs"]["batch"] == 3
+    # nothing past the backbone is merged, so nothing may follow a head
+    with pytest.raises(ValueError):
+        OG.merge_graph(g2 + [node("relu", [2])], 3)
+
+
 def check_invariants(common, merged, M):
     """What must hold for any input: every operation merged exactly once, parents before children, the
     original edges recovered when the reshapes are contracted, a reshape on exactly the Batch/Channel edges."""
@@ -91,6 +116,10 @@ def check_invariants(common, merged, M):
             assert n["dim"] == "Channel" and n["attrs"]["groups"] == M * common[n["source"]]["attrs"]["groups"]
         if n["kind"] == "layernorm":
             assert n["dim"] == "Channel" and n["attrs"]["groups"] == M
+        if n["kind"] == "task_head":
+            src = common[n["source"]]["attrs"]
+            assert n["dim"] == "Batch" and n["attrs"]["instances"] == M
+            assert {k: v for k, v in n["attrs"].items() if k != "instances"} == src
 
 
 def random_dag(rng, n):
@@ -106,6 +135,8 @@ def random_dag(rng, n):
         attrs = {"matmul": dict(K=8, Nout=8, bias=1), "conv2d": dict(cin=8, cout=8, k=3, stride=1, pad=1, groups=int(rng.choice([1, 2, 4])), bias=0),
                  "layernorm": dict(H=8), "batchnorm": dict(C=8), "attention": dict(heads=2, d=4), "maxpool": dict(k=3, stride=2, pad=1)}.get(kind, {})
         nodes.append(node(kind, parents, **attrs))
+    for _ in range(int(rng.integers(0, 3))):          # per-network layers hang off the backbone as leaves
+        nodes.append(node("task_head", [int(rng.integers(0, n))], K=8, bias=int(rng.integers(0, 2))))
     return nodes
 
 
@@ -151,7 +182,7 @@ def oracle_canon(common, M):
         if n["kind"] == "reshape_transpose":
             a = dict(n["attrs"])
         else:
-            a = {s: int(n["attrs"].get(s, M if s in ("batch", "groups") and n["kind"] in ("matmul", "layernorm", "attention") else 0))
+            a = {s: int(n["attrs"].get(s, M if s in ("batch", "groups", "instances") and n["kind"] in ("matmul", "layernorm", "attention", "task_head") else 0))
                  for s in slots}
         out.append((n["kind"], tuple(n["parents"]), n["dim"], n["source"], tuple(sorted(a.items()))))
     return out
@@ -169,6 +200,7 @@ def test_header_symbols_are_exported(NG):
 def test_merger_equals_oracle(NG):
     rng = np.random.default_rng(12)
     cases = [(G.ffnn_example(), 2), (G.encoder_stack_graph(NI.EncoderShape(layers=2)), 8),
+             (G.encoder_with_task_heads_graph(NI.EncoderShape(layers=2)), 8),
              (G.resnet_graph(NI.resnet_spec()), 32), (G.resnet_graph(NI.resnet_spec(32, 4)), 16)]
     cases += [(random_dag(rng, int(rng.integers(2, 60))), int(rng.integers(1, 9))) for _ in range(80)]
     for common, M in cases:
@@ -187,6 +219,10 @@ def test_merger_rejects_bad_arguments(NG):
     assert L.netfuse_graph_add_op(g.h, 6, None, 0, None, 0) < 0          # an operation without one
     assert L.netfuse_graph_add_op(g.h, 11, zero, 1, None, 0) < 0         # reshapes are the merger's to insert
     assert L.netfuse_graph_add_op(g.h, 99, zero, 1, None, 0) < 0
+    head = L.netfuse_graph_add_op(g.h, 12, zero, 1, None, 0)             # a task head on the input ...
+    assert head == 1 and L.netfuse_graph_merge(g.h, 2)
+    assert L.netfuse_graph_add_op(g.h, 6, (ctypes.c_int * 1)(head), 1, None, 0) == 2
+    assert not L.netfuse_graph_merge(g.h, 2)                             # ... must stay a leaf
     assert L.netfuse_graph_add_op(None, 0, None, 0, None, 0) < 0
     assert not L.netfuse_graph_merge(g.h, 0) and not L.netfuse_graph_merge(None, 2)
     assert L.netfuse_graph_size(None) < 0 and L.netfuse_graph_lower(None, None, 0) < 0
@@ -234,6 +270,19 @@ def test_lowered_resnet_equals_the_hand_written_sequence(NG, card, bw, M):
     assert merged_groups == ({M} if card == 1 else {M, M * card})
 
 
+def test_lowered_backbone_with_task_heads(NG):
+    """The encoder as a common backbone: the same calls as without heads, then ONE ragged launch for the M
+    unmerged layers, reading the last normalisation's output in the batch form (no reshape materialised)."""
+    from paper_2009_13062_amd.workloads import encoder_call_list
+    shape = NI.EncoderShape(layers=2)
+    got, calls, nodes = named_calls(NG, G.encoder_with_task_heads_graph(shape), 8)
+    assert got[:-1] == encoder_call_list(2)
+    assert got[-1] == ("linear_ragged", "head", "l1.ln2", None, 0)
+    assert all(c["layout"] == 0 for c in calls if c["call"] == "layernorm")
+    assert not any(c["call"] == "merge_transpose" for c in calls)
+    assert nodes[calls[-1]["op"]]["attrs"] == {"K": shape.hidden, "bias": 1, "instances": 8}
+
+
 def test_lowering_keeps_what_it_cannot_fold(NG):
     """A batch matmul feeding a group normalisation AND a convolution-side consumer: the reshape is real."""
     g = [node("input"), node("matmul", [0], K=8, Nout=8, bias=0), node("layernorm", [1], H=8), node("batchnorm", [2], C=8),
@@ -264,13 +313,14 @@ def test_merging_32_resnext50_takes_far_less_than_the_papers_600_ms(NG):
 
 # ------------------------------------------------------------------ a generated call list on the GPU
 @pytest.mark.gpu
-@pytest.mark.parametrize("which", ["encoder", "resnext"])
+@pytest.mark.parametrize("which", ["encoder", "resnext", "encoder_heads"])
 def test_generated_call_list_runs_like_the_hand_written_forward(NG, oracle, which):
     import torch
     from oracle import models as OM
     from paper_2009_13062_amd.workloads import EncoderStack, ResNetForward
     M = 3
-    if which == "encoder":
+    heads = None
+    if which in ("encoder", "encoder_heads"):
         shape = NI.EncoderShape(hidden=128, heads=2, ffn=256, layers=2, seq=64)
         inp = NI.encoder_stack(M, shape, bf16=True)
         net = EncoderStack.from_numpy(inp, M, 1, shape.seq, shape.heads)
@@ -285,6 +335,16 @@ def test_generated_call_list_runs_like_the_hand_written_forward(NG, oracle, whic
                             p + "ln1": dict(gamma=Lw["ln1_g"], beta=Lw["ln1_b"]), p + "ln2": dict(gamma=Lw["ln2_g"], beta=Lw["ln2_b"])})
         ref = OM.encoder_stack(inp, M, 1, shape.seq, shape.heads, out_bf16=True)
         last, seq = "l%d.ln2" % (shape.layers - 1), shape.seq
+        if which == "encoder_heads":
+            # networks fine-tuned for tasks with 2, 5 and 3 classes: one fully connected layer each on the backbone
+            common = G.encoder_with_task_heads_graph(shape)
+            nout = [2, 5, 3]
+            rng = np.random.default_rng(5)
+            Wh = [NI.on_bf16_grid((rng.standard_normal((shape.hidden, n)) * 0.05).astype(np.float32)) for n in nout]
+            bh = [(rng.standard_normal(n) * 0.05).astype(np.float32) for n in nout]
+            weights["head"] = dict(W=torch.from_numpy(np.concatenate([w.ravel() for w in Wh])).to("cuda", torch.bfloat16),
+                                   b=torch.from_numpy(np.concatenate(bh)).cuda(), nout=nout)
+            heads = (Wh, bh, nout)
     else:
         spec = NI.resnet_spec(cardinality=8, base_width=8, image=64, width_div=2, depths=(1, 1, 1, 1))
         inp = NI.resnet_params(spec, M, bf16=True)
@@ -307,3 +367,15 @@ def test_generated_call_list_runs_like_the_hand_written_forward(NG, oracle, whic
     assert torch.equal(got, want), "the generated call list and the hand-written forward run the same calls"
     err = np.abs(got.float().cpu().numpy() - ref)
     assert float(err.max()) < 0.15 * max(1.0, float(np.abs(ref).max()))
+    if heads is not None:
+        import paper_2009_13062_amd as nf
+        Wh, bh, nout = heads
+        head_id = [i for i, n in enumerate(nodes) if n["kind"] == "task_head"][0]
+        ys = nf.ragged_views(T[head_id], shape.seq, nout)
+        # the oracle's per-network layers on the oracle's own backbone output (end-to-end bound as above; the
+        # ragged launch has its per-operator parity tests of its own)
+        want_h = oracle.linear_ragged(ref, Wh, bh, out_bf16=True)
+        for m in range(M):
+            assert tuple(ys[m].shape) == want_h[m].shape == (shape.seq, nout[m])
+            e = np.abs(ys[m].float().cpu().numpy() - want_h[m])
+            assert float(e.max()) <= 0.15 * max(1.0, float(np.abs(want_h[m]).max())), (m, float(e.max()))
