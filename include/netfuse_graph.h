@@ -26,6 +26,8 @@
  *   NF_OP_MAXPOOL      { k, stride, pad }
  *   NF_OP_RESHAPE_TRANSPOSE { from_dim, to_dim }                 merged graphs only
  *   NF_OP_TASK_HEAD    { K, has_bias, instances }                instances: 1 -> M (M unmerged layers)
+ *   NF_OP_ATTENTION_RELPOS { heads, d, batch }                   batch: 1 -> M; parents: the packed Q|K|V tensor,
+ *                                                                then the projected position encodings
  *   others             none
  * Trailing slots that are not passed default to 1 for batch / groups / instances and to 0 otherwise.
  *
@@ -49,7 +51,8 @@ typedef struct nf_graph nf_graph;
 typedef enum {
   NF_OP_INPUT = 0, NF_OP_MATMUL = 1, NF_OP_CONV2D = 2, NF_OP_LAYERNORM = 3, NF_OP_BATCHNORM = 4,
   NF_OP_ATTENTION = 5, NF_OP_RELU = 6, NF_OP_GELU = 7, NF_OP_ADD = 8, NF_OP_MAXPOOL = 9,
-  NF_OP_AVGPOOL_GLOBAL = 10, NF_OP_RESHAPE_TRANSPOSE = 11, NF_OP_TASK_HEAD = 12
+  NF_OP_AVGPOOL_GLOBAL = 10, NF_OP_RESHAPE_TRANSPOSE = 11, NF_OP_TASK_HEAD = 12,
+  NF_OP_ATTENTION_RELPOS = 13
 } nf_op_kind;
 
 /* d_i of Algorithm 1: the dimension along which the tensors of the M instances are concatenated */
@@ -85,6 +88,8 @@ int netfuse_graph_get_op(const nf_graph* g, int id, int* kind, int* concat_dim, 
  *   matmul [-> gelu | relu] [-> add(residual)]              one netfuse_linear (act before the residual)
  *   [reshape ->] layernorm [-> reshape]                     one netfuse_layernorm in the producer's layout
  *   attention, maxpool, avgpool_global                      one call each
+ *   relative-position attention                             one netfuse_attention_relpos; the call's `residual`
+ *                                                            field names its second operand (the positions)
  *   any other reshape                                       netfuse_merge_transpose
  *   task head (M unmerged fully connected layers)           one netfuse_linear_ragged: the M layers in one
  *                                                            launch, each with its own output width (the
@@ -95,14 +100,16 @@ int netfuse_graph_get_op(const nf_graph* g, int id, int* kind, int* concat_dim, 
  */
 typedef enum {
   NF_CALL_LINEAR = 0, NF_CALL_CONV2D = 1, NF_CALL_LAYERNORM = 2, NF_CALL_ATTENTION = 3, NF_CALL_MAXPOOL = 4,
-  NF_CALL_AVGPOOL_GLOBAL = 5, NF_CALL_MERGE_TRANSPOSE = 6, NF_CALL_UNFUSED = 7, NF_CALL_LINEAR_RAGGED = 8
+  NF_CALL_AVGPOOL_GLOBAL = 5, NF_CALL_MERGE_TRANSPOSE = 6, NF_CALL_UNFUSED = 7, NF_CALL_LINEAR_RAGGED = 8,
+  NF_CALL_ATTENTION_RELPOS = 9
 } nf_call_kind;
 
 typedef struct {
   int call;       /* nf_call_kind */
   int op;         /* merged operation that carries the weights / attributes (matmul, conv2d, layernorm, ...) */
   int input;      /* merged operation whose output tensor is this call's input */
-  int residual;   /* merged operation whose output is added in the epilogue, or -1 */
+  int residual;   /* merged operation whose output is added in the epilogue, or -1
+                     (NF_CALL_ATTENTION_RELPOS: the operation that produces the projected position encodings) */
   int output;     /* last merged operation folded into the call: its output tensor is the call's output */
   int act;        /* nf_act of the epilogue */
   int batchnorm;  /* folded batch normalisation operation (conv2d), or -1 */

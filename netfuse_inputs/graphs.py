@@ -6,7 +6,8 @@ subgraph down for the architectures of the workloads: a list of nodes, each a di
 (parents always precede children).  No merging logic lives here: the C++ merger of the library and the
 Python oracle both take these lists as their input.
 
-kinds: input, matmul, conv2d, layernorm, batchnorm, attention, relu, gelu, add, maxpool, avgpool_global,
+kinds: input, matmul, conv2d, layernorm, batchnorm, attention, attention_relpos, relu, gelu, add, maxpool,
+avgpool_global,
 task_head (a fully connected layer outside the common backbone: Section 3.2, last paragraph; Section 6)
 """
 from __future__ import annotations
@@ -36,12 +37,18 @@ def ffnn_example(K: int = 64, Nout: int = 64) -> List[Node]:
     return g.nodes
 
 
-def encoder_layer(g: GraphBuilder, x: int, shape: EncoderShape, prefix: str) -> int:
+def encoder_layer(g: GraphBuilder, x: int, shape: EncoderShape, prefix: str, r: int = -1) -> int:
     """The residual additions name the matmul branch first: where the two operands of an addition disagree on
-    the concatenation dimension one against one, Algorithm 1's vote goes to the first parent."""
+    the concatenation dimension one against one, Algorithm 1's vote goes to the first parent.
+    r: the node of the relative position encodings; with it the layer is XLNet-shaped (its own projection of the
+    encodings, attention with the relative-position term)."""
     Hd, F = shape.hidden, shape.ffn
     qkv = g.add("matmul", [x], name=prefix + "qkv", K=Hd, Nout=3 * Hd, bias=1)
-    att = g.add("attention", [qkv], name=prefix + "attention", heads=shape.heads, d=shape.head_dim)
+    if r < 0:
+        att = g.add("attention", [qkv], name=prefix + "attention", heads=shape.heads, d=shape.head_dim)
+    else:
+        kr = g.add("matmul", [r], name=prefix + "kr", K=Hd, Nout=Hd, bias=0)
+        att = g.add("attention_relpos", [qkv, kr], name=prefix + "attention", heads=shape.heads, d=shape.head_dim)
     o = g.add("matmul", [att], name=prefix + "o", K=Hd, Nout=Hd, bias=1)
     h = g.add("add", [o, x], name=prefix + "add1")
     x1 = g.add("layernorm", [h], name=prefix + "ln1", H=Hd)
@@ -58,6 +65,16 @@ def encoder_stack_graph(shape: EncoderShape) -> List[Node]:
     x = g.add("input", name="x")
     for L in range(shape.layers):
         x = encoder_layer(g, x, shape, "l%d." % L)
+    return g.nodes
+
+
+def xlnet_stack_graph(shape: EncoderShape) -> List[Node]:
+    """The XLNet-shaped stack: two inputs (the token embeddings and the relative position encodings)."""
+    g = GraphBuilder()
+    x = g.add("input", name="x")
+    r = g.add("input", name="r")
+    for L in range(shape.layers):
+        x = encoder_layer(g, x, shape, "l%d." % L, r)
     return g.nodes
 
 

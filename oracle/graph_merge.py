@@ -39,8 +39,8 @@ def merge_op(node: Dict, M: int):
     """Merge(op_i, {w_ij}): the merged operation's attributes and required concatenation dimension.
     matmul -> batch matmul over M weight sets (Batch); convolution -> grouped convolution with M times the
     groups and channels (Channel); layer normalisation -> group normalisation with M groups (Channel); batch
-    normalisation -> M times the channels (Channel); attention, already a batch of independent
-    problems, -> M times the problems (Batch); operations without weights are unchanged (DontCare)."""
+    normalisation -> M times the channels (Channel); attention (plain or with the relative-position term), already
+    a batch of independent problems, -> M times the problems (Batch); operations without weights are unchanged (DontCare)."""
     kind, a = node["kind"], dict(node["attrs"])
     if kind == "matmul":
         a["batch"] = a.get("batch", 1) * M
@@ -54,7 +54,7 @@ def merge_op(node: Dict, M: int):
     if kind == "batchnorm":
         a["C"] = a["C"] * M
         return a, CHANNEL
-    if kind == "attention":
+    if kind in ("attention", "attention_relpos"):
         a["batch"] = a.get("batch", 1) * M
         return a, BATCH
     if kind == "task_head":

@@ -22,7 +22,7 @@ struct Op {
   long attrs[NF_GRAPH_MAX_ATTRS];
 };
 
-bool valid_kind(int k) { return k >= NF_OP_INPUT && k <= NF_OP_TASK_HEAD; }
+bool valid_kind(int k) { return k >= NF_OP_INPUT && k <= NF_OP_ATTENTION_RELPOS; }
 
 // slot of the "how many independent weight sets" attribute, or -1
 int count_slot(int kind) {
@@ -31,6 +31,7 @@ int count_slot(int kind) {
     case NF_OP_LAYERNORM: return 1;
     case NF_OP_ATTENTION: return 2;
     case NF_OP_TASK_HEAD: return 2;
+    case NF_OP_ATTENTION_RELPOS: return 2;
   }
   return -1;
 }
@@ -44,7 +45,8 @@ int merge_op(Op& m, int M) {
       return NF_DIM_CHANNEL;
     case NF_OP_LAYERNORM: m.attrs[1] *= M; return NF_DIM_CHANNEL;        // group normalisation with M groups
     case NF_OP_BATCHNORM: m.attrs[0] *= M; return NF_DIM_CHANNEL;        // per channel: concatenated channels
-    case NF_OP_ATTENTION: m.attrs[2] *= M; return NF_DIM_BATCH;          // M times the independent problems
+    case NF_OP_ATTENTION:                                                // M times the independent problems
+    case NF_OP_ATTENTION_RELPOS: m.attrs[2] *= M; return NF_DIM_BATCH;   // (its two query biases: one pair per model)
     // outside the common backbone (Section 3.2, last paragraph): not merged -- M instances of the layer as it
     // is, each on its own network's rows, which are contiguous in the batch-concatenated form
     case NF_OP_TASK_HEAD: m.attrs[2] *= M; return NF_DIM_BATCH;
@@ -260,6 +262,11 @@ int netfuse_graph_lower(const nf_graph* merged, nf_call* calls, int cap) {
       }
       case NF_OP_TASK_HEAD: c.call = NF_CALL_LINEAR_RAGGED; break;
       case NF_OP_ATTENTION: c.call = NF_CALL_ATTENTION; break;
+      case NF_OP_ATTENTION_RELPOS:
+        if (op.parents.size() != 2) break;                 // NF_CALL_UNFUSED: not the two-operand form
+        c.call = NF_CALL_ATTENTION_RELPOS;
+        c.residual = op.parents[1];
+        break;
       case NF_OP_MAXPOOL: c.call = NF_CALL_MAXPOOL; break;
       case NF_OP_AVGPOOL_GLOBAL: c.call = NF_CALL_AVGPOOL_GLOBAL; break;
       case NF_OP_BATCHNORM: case NF_OP_RELU: case NF_OP_GELU: case NF_OP_ADD: break;       // NF_CALL_UNFUSED

@@ -13,10 +13,10 @@ from typing import Dict, List, Sequence
 from . import lib as _lib
 
 KINDS = ("input", "matmul", "conv2d", "layernorm", "batchnorm", "attention", "relu", "gelu", "add", "maxpool",
-         "avgpool_global", "reshape_transpose", "task_head")
+         "avgpool_global", "reshape_transpose", "task_head", "attention_relpos")
 DIMS = ("Batch", "Channel", "DontCare")
 CALLS = ("linear", "conv2d", "layernorm", "attention", "maxpool2d", "avgpool_global", "merge_transpose", "unfused",
-         "linear_ragged")
+         "linear_ragged", "attention_relpos")
 # attribute slots per kind (include/netfuse_graph.h)
 SLOTS = {
     "matmul": ("K", "Nout", "bias", "batch"),
@@ -27,6 +27,7 @@ SLOTS = {
     "maxpool": ("k", "stride", "pad"),
     "reshape_transpose": ("from", "to"),
     "task_head": ("K", "bias", "instances"),
+    "attention_relpos": ("heads", "d", "batch"),
 }
 _DEFAULT_ONE = ("batch", "groups", "instances")
 MAX_ATTRS = 8
@@ -113,13 +114,15 @@ def run_calls(calls, merged_nodes, common_nodes, M, graph_input, weights, batch=
     """Executes a lowered call list.  ``weights[name]`` holds the merged parameters of the operation of the
     common subgraph called ``name``: matmul {"W", "b"}, layernorm {"gamma", "beta"}, conv2d {"w"} and, for the
     batch normalisation folded into it, {"scale", "shift"} under the batch norm's own name; a task head
-    {"W", "b", "nout"}: the M unmerged layers' weights and biases one after another and their output widths.
+    {"W", "b", "nout"}: the M unmerged layers' weights and biases one after another and their output widths; a
+    relative-position attention {"rwb", "rrb"}.  ``graph_input``: the tensor of the graph's input, or
+    {input name: tensor} when it has several.
     Returns {merged operation id: output tensor}."""
     import paper_2009_13062_amd as nf
     T = {}
     for i, nd in enumerate(merged_nodes):
         if nd["kind"] == "input":
-            T[i] = graph_input
+            T[i] = graph_input[common_nodes[nd["source"]]["name"]] if isinstance(graph_input, dict) else graph_input
     name_of = lambda op: common_nodes[merged_nodes[op]["source"]]["name"]
     for c in calls:
         nd = merged_nodes[c["op"]]
@@ -139,6 +142,9 @@ def run_calls(calls, merged_nodes, common_nodes, M, graph_input, weights, batch=
             y = nf.layernorm(x, w["gamma"], w["beta"], M, eps=eps, layout=c["layout"])
         elif c["call"] == "attention":
             y = nf.attention_packed(x, batch, seq, nd["attrs"]["heads"])
+        elif c["call"] == "attention_relpos":
+            w = weights[name_of(c["op"])]
+            y = nf.attention_relpos_packed(x, res, batch, seq, nd["attrs"]["heads"], bias_w=w.get("rwb"), bias_r=w.get("rrb"))
         elif c["call"] == "maxpool2d":
             a = nd["attrs"]
             y = nf.maxpool2d(x, a["k"], a["stride"], a["pad"])

@@ -115,14 +115,18 @@ class EncoderStack:
         return out
 
 
-def encoder_call_list(layers: int):
+def encoder_call_list(layers: int, rel: bool = False):
     """The calls of EncoderStack.forward as data: (entry point, operation, producer of the input, producer of
-    the residual or None, activation), operations and producers named as in netfuse_inputs.graphs."""
+    the residual -- for the relative-position attention: of its second operand -- or None, activation),
+    operations and producers named as in netfuse_inputs.graphs.  rel: the XLNet-shaped stack."""
     out, x = [], "x"
     for L in range(layers):
         p = "l%d." % L
-        out += [("linear", p + "qkv", x, None, nf.ACT_NONE),
-                ("attention", p + "attention", p + "qkv", None, nf.ACT_NONE),
+        out += [("linear", p + "qkv", x, None, nf.ACT_NONE)]
+        out += [("linear", p + "kr", "r", None, nf.ACT_NONE),
+                ("attention_relpos", p + "attention", p + "qkv", p + "kr", nf.ACT_NONE)] if rel else [
+                ("attention", p + "attention", p + "qkv", None, nf.ACT_NONE)]
+        out += [
                 ("linear", p + "o", p + "attention", x, nf.ACT_NONE),
                 ("layernorm", p + "ln1", p + "o", None, nf.ACT_NONE),
                 ("linear", p + "ffn1", p + "ln1", None, nf.ACT_GELU),

@@ -110,7 +110,7 @@ def check_invariants(common, merged, M):
             assert {merged[p]["dim"], n["dim"]} != {"Batch", "Channel"}
             if merged[p]["kind"] == "reshape_transpose":
                 assert merged[p]["dim"] == n["dim"]
-        if n["kind"] in ("matmul", "attention"):
+        if n["kind"] in ("matmul", "attention", "attention_relpos"):
             assert n["dim"] == "Batch" and n["attrs"]["batch"] == M * common[n["source"]]["attrs"].get("batch", 1)
         if n["kind"] == "conv2d":
             assert n["dim"] == "Channel" and n["attrs"]["groups"] == M * common[n["source"]]["attrs"]["groups"]
@@ -146,7 +146,8 @@ def test_oracle_invariants_on_random_graphs_and_workloads():
         g = random_dag(rng, int(rng.integers(2, 40)))
         M = int(rng.integers(1, 6))
         check_invariants(g, OG.merge_graph(g, M), M)
-    for g in (G.encoder_stack_graph(NI.EncoderShape(layers=3)), G.resnet_graph(NI.resnet_spec()), G.resnet_graph(NI.resnet_spec(32, 4))):
+    for g in (G.encoder_stack_graph(NI.EncoderShape(layers=3)), G.resnet_graph(NI.resnet_spec()), G.resnet_graph(NI.resnet_spec(32, 4)),
+              G.xlnet_stack_graph(NI.EncoderShape(layers=3)), G.encoder_with_task_heads_graph(NI.EncoderShape(layers=2))):
         check_invariants(g, OG.merge_graph(g, 32), 32)
     # a ResNet is channel-merged throughout: no reshape at all; M = 1 changes nothing but the tags
     assert not any(n["kind"] == "reshape_transpose" for n in OG.merge_graph(G.resnet_graph(NI.resnet_spec()), 32))
@@ -182,7 +183,7 @@ def oracle_canon(common, M):
         if n["kind"] == "reshape_transpose":
             a = dict(n["attrs"])
         else:
-            a = {s: int(n["attrs"].get(s, M if s in ("batch", "groups", "instances") and n["kind"] in ("matmul", "layernorm", "attention", "task_head") else 0))
+            a = {s: int(n["attrs"].get(s, M if s in ("batch", "groups", "instances") and n["kind"] in ("matmul", "layernorm", "attention", "task_head", "attention_relpos") else 0))
                  for s in slots}
         out.append((n["kind"], tuple(n["parents"]), n["dim"], n["source"], tuple(sorted(a.items()))))
     return out
@@ -201,6 +202,7 @@ def test_merger_equals_oracle(NG):
     rng = np.random.default_rng(12)
     cases = [(G.ffnn_example(), 2), (G.encoder_stack_graph(NI.EncoderShape(layers=2)), 8),
              (G.encoder_with_task_heads_graph(NI.EncoderShape(layers=2)), 8),
+             (G.xlnet_stack_graph(NI.EncoderShape(layers=3)), 32),
              (G.resnet_graph(NI.resnet_spec()), 32), (G.resnet_graph(NI.resnet_spec(32, 4)), 16)]
     cases += [(random_dag(rng, int(rng.integers(2, 60))), int(rng.integers(1, 9))) for _ in range(80)]
     for common, M in cases:
@@ -270,6 +272,19 @@ def test_lowered_resnet_equals_the_hand_written_sequence(NG, card, bw, M):
     assert merged_groups == ({M} if card == 1 else {M, M * card})
 
 
+def test_lowered_xlnet_stack_equals_the_hand_written_sequence(NG):
+    """Two inputs: the breadth-first traversal reaches every layer's position projection from the encodings
+    early, so the calls come in another (valid: named_calls checks every operand exists) order than the
+    hand-written forward issues them; call by call they are the same."""
+    from paper_2009_13062_amd.workloads import encoder_call_list
+    got, calls, nodes = named_calls(NG, G.xlnet_stack_graph(NI.EncoderShape(layers=3)), 32)
+    want = encoder_call_list(3, rel=True)
+    assert sorted(got, key=str) == sorted(want, key=str) and len(got) == 3 * 8
+    rel = [nodes[c["op"]] for c in calls if c["call"] == "attention_relpos"]
+    assert len(rel) == 3 and all(n["attrs"]["batch"] == 32 and n["dim"] == "Batch" for n in rel)
+    assert not any(c["call"] in ("merge_transpose", "unfused") for c in calls)
+
+
 def test_lowered_backbone_with_task_heads(NG):
     """The encoder as a common backbone: the same calls as without heads, then ONE ragged launch for the M
     unmerged layers, reading the last normalisation's output in the batch form (no reshape materialised)."""
@@ -313,26 +328,30 @@ def test_merging_32_resnext50_takes_far_less_than_the_papers_600_ms(NG):
 
 # ------------------------------------------------------------------ a generated call list on the GPU
 @pytest.mark.gpu
-@pytest.mark.parametrize("which", ["encoder", "resnext", "encoder_heads"])
+@pytest.mark.parametrize("which", ["encoder", "resnext", "encoder_heads", "xlnet"])
 def test_generated_call_list_runs_like_the_hand_written_forward(NG, oracle, which):
     import torch
     from oracle import models as OM
     from paper_2009_13062_amd.workloads import EncoderStack, ResNetForward
     M = 3
     heads = None
-    if which in ("encoder", "encoder_heads"):
+    if which in ("encoder", "encoder_heads", "xlnet"):
         shape = NI.EncoderShape(hidden=128, heads=2, ffn=256, layers=2, seq=64)
-        inp = NI.encoder_stack(M, shape, bf16=True)
+        inp = NI.encoder_stack(M, shape, bf16=True, rel=which == "xlnet")
         net = EncoderStack.from_numpy(inp, M, 1, shape.seq, shape.heads)
         x = torch.from_numpy(inp["X"]).to("cuda", torch.bfloat16)
         want = net.forward(x).clone()
-        common = G.encoder_stack_graph(shape)
+        common = G.xlnet_stack_graph(shape) if which == "xlnet" else G.encoder_stack_graph(shape)
+        if which == "xlnet":
+            x = {"x": x, "r": net.buf["Rrep"]}
         weights = {}
         for L, Lw in enumerate(net.layers):
             p = "l%d." % L
             weights.update({p + "qkv": dict(W=Lw["Wqkv"], b=Lw["bqkv"]), p + "o": dict(W=Lw["Wo"], b=Lw["bo"]),
                             p + "ffn1": dict(W=Lw["W1"], b=Lw["b1"]), p + "ffn2": dict(W=Lw["W2"], b=Lw["b2"]),
                             p + "ln1": dict(gamma=Lw["ln1_g"], beta=Lw["ln1_b"]), p + "ln2": dict(gamma=Lw["ln2_g"], beta=Lw["ln2_b"])})
+            if which == "xlnet":
+                weights.update({p + "kr": dict(W=Lw["Wr"]), p + "attention": dict(rwb=Lw["rwb"], rrb=Lw["rrb"])})
         ref = OM.encoder_stack(inp, M, 1, shape.seq, shape.heads, out_bf16=True)
         last, seq = "l%d.ln2" % (shape.layers - 1), shape.seq
         if which == "encoder_heads":
