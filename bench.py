@@ -629,7 +629,8 @@ def main():
                 others[name] = dict(ms_per_step=r["ms_per_step"], ms_per_step_std=r["ms_per_step_std"],
                                     inferences_per_s=r["inferences_per_s"], steps=args.steps,
                                     separate_ms=r["separate_ms"], speedup_vs_separate=r["speedup_vs_separate"],
-                                    model_TFLOPs=r["model_TFLOPs"], weight_copies_rotated=r["config"]["weight_copies_rotated"],
+                                    model_TFLOPs=r["model_TFLOPs"], kernel_time_ms_per_step=r["kernel_time_ms_per_step"],
+                                    weight_copies_rotated=r["config"]["weight_copies_rotated"],
                                     roofline=r["roofline"], kernels=dict(list(r["kernels"].items())[:8]))
                 log("[bench] %s: %.3f +- %.3f ms/step, %.2fx vs separate (%.1f s)" % (
                     name, r["ms_per_step"], r["ms_per_step_std"], r["speedup_vs_separate"], time.time() - t1))
