@@ -540,15 +540,22 @@ def test_runs_are_bit_reproducible(nf):
 
 
 # ------------------------------------------------------------------ whole workloads, reduced and full size
-def _encoder_per_call_parity(oracle, trace_layer, X_in, Lw_host, m_list, batch, seq, heads, dtype):
-    """Each call of one layer against the oracle on the GPU's own input to that call."""
+def _encoder_per_call_parity(oracle, trace_layer, X_in, Lw_host, m_list, batch, seq, heads, dtype, R=None):
+    """Each call of one layer against the oracle on the GPU's own input to that call.  R: the relative position
+    encodings of an XLNet-shaped layer (position projection, then attention with the position term)."""
     bf = dtype == torch.bfloat16
     t = {k: host(v[m_list]) for k, v in trace_layer.items()}
     X = host(X_in[m_list])
     M = len(m_list)
     L = Lw_host
     check(t["qkv"], oracle.linear(X, L["Wqkv"], bias=L["bqkv"], out_bf16=bf), dtype, "qkv")
-    check(t["att"], oracle.attention_packed(t["qkv"], batch, seq, heads, out_bf16=bf), dtype, "attention")
+    if R is None:
+        check(t["att"], oracle.attention_packed(t["qkv"], batch, seq, heads, out_bf16=bf), dtype, "attention")
+    else:
+        Rrep = np.broadcast_to(R, (M,) + R.shape).copy()
+        check(t["kr"], oracle.linear(Rrep, L["Wr"], out_bf16=bf), dtype, "position projection")
+        check(t["att"], oracle.attention_relpos_packed(t["qkv"], t["kr"], batch, seq, heads, bias_w=L["rwb"], bias_r=L["rrb"],
+                                                       out_bf16=bf), dtype, "relative attention")
     check(t["h"], oracle.linear(t["att"], L["Wo"], bias=L["bo"], residual=X, out_bf16=bf), dtype, "o-proj")
     check(t["x1"], oracle.layernorm(t["h"], L["ln1_g"], L["ln1_b"], M, out_bf16=bf), dtype, "ln1")
     check(t["f1"], oracle.linear(t["x1"], L["W1"], bias=L["b1"], act=2, out_bf16=bf), dtype, "ffn1+gelu")
@@ -589,17 +596,21 @@ def test_encoder_layer_workload2_full_size(nf, oracle):
     assert float(err.max()) < 0.15 and float(err.mean()) < 0.01, (float(err.max()), float(err.mean()))
 
 
-@pytest.mark.parametrize("seq,packed", [(128, False), (128, True), (512, False), (512, True)])
-def test_encoder_stack_workload5_full_size_sampled(nf, oracle, seq, packed):
-    """Workload 5 in the configuration bench.py times: M = 32, 12 layers, hidden 768, bf16, on row-major and
-    on packed weights (bench.py's default).  The first and last layers are checked call by call for sampled
-    models on the GPU's own inputs."""
+@pytest.mark.parametrize("seq,packed,rel", [(128, False, False), (128, True, False), (512, False, False), (512, True, False),
+                                            (128, True, True)])
+def test_encoder_stack_workload5_full_size_sampled(nf, oracle, seq, packed, rel):
+    """Workload 5 in the configurations bench.py times: M = 32, 12 layers, hidden 768, bf16, on row-major and
+    on packed weights (bench.py's default), and the XLNet-shaped stack.  The first and last layers are checked
+    call by call for sampled models on the GPU's own inputs; then the whole 12-layer chain of sampled models
+    against the oracle run on the seeded inputs alone."""
     from netfuse_inputs.device import encoder_stack_device
+    from oracle import models as OM
     from paper_2009_13062_amd.workloads import EncoderStack
     M, shape = 32, NI.EncoderShape(layers=12, seq=seq)
-    inp = encoder_stack_device(M, shape, cfg=5)
-    enc = EncoderStack(inp["layers"], M, 1, seq, shape.heads, packed=packed)
+    inp = encoder_stack_device(M, shape, cfg=5, rel=rel)
+    enc = EncoderStack(inp["layers"], M, 1, seq, shape.heads, packed=packed, R=inp.get("R"))
     assert not packed or all(k + "_p" in enc.layers[0] for k in ("Wqkv", "Wo", "W1", "W2"))
+    Rh = host(inp["R"]) if rel else None
     trace = []
     out = enc.forward(inp["X"], trace)
     assert torch.isfinite(out.float()).all()
@@ -607,7 +618,16 @@ def test_encoder_stack_workload5_full_size_sampled(nf, oracle, seq, packed):
     for li in (0, 11):
         X_in = inp["X"] if li == 0 else trace[li - 1]["x2"]
         _encoder_per_call_parity(oracle, trace[li], X_in, _slice_layer(enc.layers[li], sample, shape.hidden),
-                                 sample, 1, seq, shape.heads, torch.bfloat16)
+                                 sample, 1, seq, shape.heads, torch.bfloat16, R=Rh)
+    # end to end: nothing of the expected value comes from the GPU path
+    e2e = [0, 31] if seq == 128 else [13]
+    sub = dict(X=host(inp["X"][e2e]), layers=[_slice_layer(Lw, e2e, shape.hidden) for Lw in enc.layers])
+    if rel:
+        sub["R"] = Rh
+    ref = OM.encoder_stack(sub, len(e2e), 1, seq, shape.heads, out_bf16=True)
+    err = np.abs(host(out[e2e]) - ref)
+    print("end-to-end over 12 layers: max abs err %.4f mean %.5f" % (float(err.max()), float(err.mean())))
+    assert float(err.max()) < 0.15 and float(err.mean()) < 0.012, (float(err.max()), float(err.mean()))
     # merged == one model at a time, bit for bit, on a sampled model
     # (row-major weights only: every kernel of that path sums k in the same order whatever tile it picks, while
     # the packed kernels split k over wavefronts for some model counts and not for others)
@@ -761,6 +781,18 @@ def test_resnet_full_size_sampled(nf, oracle, name, M, card, bw, cfg):
     out = net.forward(inp["x"])
     assert torch.isfinite(out.float()).all()
     _resnet_per_call_parity(oracle, net, inp["x"], spec, [0, M // 2, M - 1])
+    # end to end for one model: nothing of the expected value comes from the GPU path
+    from oracle import models as OM
+    m = M // 2
+    P = {}
+    for c in spec.convs():
+        sl = slice(m * c.cout, (m + 1) * c.cout)
+        P[c.name] = {k: host(v[sl]) for k, v in inp["params"][c.name].items()}
+    ref = OM.resnet_forward(dict(x=host(inp["x"][:, 3 * m:3 * m + 3]), params=P), spec, 1, out_bf16=True)
+    C = spec.out_channels
+    err = np.abs(host(out[:, m * C:(m + 1) * C]) - ref)
+    print("end-to-end over %d convolutions: max abs err %.4f, max |ref| %.3f" % (len(spec.convs()), float(err.max()), float(np.abs(ref).max())))
+    assert float(err.max()) < 0.1 * max(1.0, float(np.abs(ref).max())), float(err.max())
 
 
 # ------------------------------------------------------------------ degenerate and extreme shapes
