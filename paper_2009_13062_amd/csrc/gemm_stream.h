@@ -35,15 +35,23 @@ __device__ __forceinline__ void reg_epilogue(f32x16_t (&acc)[FM][FN], bf16_t* C,
                                              const float* col_bias, int row_base, int col_base) {
   const int lane = threadIdx.x % kWave;
   const int half = lane / 32, l32 = lane % 32;
+  // Row blocks outermost: the column blocks of a row block are stored one right after the other, so the 64-byte
+  // halves of a 128-byte output line (two neighbouring column blocks of one wavefront) reach L2 close together.
+  // With the column blocks outermost they were four row blocks of epilogue arithmetic apart, and L2 wrote a
+  // third of the lines back half filled: 135.7 MB written for a 100.7 MB output (768 -> 3072 + GELU at 512 rows
+  // and 32 models), 120 us against 108 us this way.
+  float4 cball[FN][4];
 #pragma unroll
-  for (int j = 0; j < FN; ++j) {
-    const int colb = col_base + j * 32;
-    float4 cb[4];
+  for (int j = 0; j < FN; ++j)
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      cb[q] = col_bias ? *reinterpret_cast<const float4*>(col_bias + colb + q * 8 + half * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+      cball[j][q] = col_bias ? *reinterpret_cast<const float4*>(col_bias + col_base + j * 32 + q * 8 + half * 4) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
+  for (int i = 0; i < FM; ++i) {
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int colb = col_base + j * 32;
+      float4 (&cb)[4] = cball[j];
       // this lane's two 8-column pieces: columns colb + 16 qq + 8 half + 0..7
       const long off = (long)(row_base + i * 32 + l32) * ldc + colb + half * 8;
       uint4 rr[2];
