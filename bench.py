@@ -158,10 +158,10 @@ class OpTimer:
             setattr(self.nf, k, v)
         self.nf.time_next_launch(None, None)
 
-    def drop_after(self, keep):
-        """Forget the records past the first `keep` (their events go back to the pool after the next synchronisation)."""
-        self.dropped = getattr(self, "dropped", []) + self.records[keep:]
-        self.records = self.records[:keep]
+    def keep_only(self, lo, hi):
+        """Forget the records outside [lo, hi) (their events go back to the pool after the next synchronisation)."""
+        self.dropped = getattr(self, "dropped", []) + self.records[:lo] + self.records[hi:]
+        self.records = self.records[lo:hi]
 
     def summary(self):
         self.torch.cuda.synchronize()
@@ -363,19 +363,25 @@ def calibrate_copy(torch, nf):
                                          "bytes_written_per_launch": dst.numel() * 2}}))
 
 
-def kernel_pass(torch, nf, events, fn, npass):
-    """npass eager steps with every launch timed by its own device timestamps."""
+def kernel_pass(torch, nf, events, fn, npass, lead=None):
+    """npass eager steps with every launch timed by its own device timestamps, inside one uninterrupted run of
+    launches: `lead` passes before them and one behind are launched the same way and their records dropped.
+    The passes in front carry the first-use costs of the timed launch path (events, the extended launch call per
+    kernel function) and bring the device to the state it has in a sustained run -- measured from idle, the
+    matrix-bound kernels of the 512-token workload read 3 - 4 % shorter than in the timed loop of steps and in a
+    rocprofv3 trace of the same command.  The pass behind is there because the last launches before the closing
+    synchronisation have read 0.4 - 2 ms on one workload (a 23 us kernel, the same launch every time) with
+    nothing to match in the step times (30 steps of 0.828 +- 0.002 ms)."""
+    lead = max(2, npass) if lead is None else lead
     with OpTimer(nf, torch, events) as ot:
-        fn()                     # the timed launch path has first-use costs of its own (events, the extended launch
-        ot.summary()             # call per kernel function): one pass through it is warm-up and is dropped
+        for _ in range(lead):
+            fn()
+        skip = len(ot.records)
         for _ in range(npass):
             fn()
-        # ... and one pass behind: the last launches before the closing synchronisation have read 0.4 - 2 ms on
-        # one workload (a 23 us kernel, the same launch every time) with nothing to match in the step times
-        # (30 steps of 0.828 +- 0.002 ms), so the records kept are those with launches on both sides
         keep = len(ot.records)
         fn()
-        ot.drop_after(keep)
+        ot.keep_only(skip, keep)
         return ot.summary()
 
 

@@ -3,7 +3,9 @@
 Every ``profiles/<workload>.md`` ends with an ``agreement:`` line written by the run that produced it: the
 average duration of the dominant kernel family as bench.py measured it (device timestamps of each launch, the
 same command run without the profiler) and as ``rocprofv3 --kernel-trace --stats`` reports it for that command.
-The two must agree within 3 %, and the roofline fraction derived from either must match the bytes stated.
+The two must agree within 3 % (or 0.6 us where that is more: between two runs of the same command the average of
+the 15 us launches of the ResNeXt workload moves by 0.5 us, 15.2 ... 15.7, while its step time stays at
+0.828 - 0.830 ms), and the roofline fraction derived from either must match the bytes stated.
 """
 import glob
 import json
@@ -31,7 +33,7 @@ def test_every_workload_has_a_summary():
 def test_bench_and_rocprof_durations_agree(path):
     a = agreement(path)
     bench_us, prof_us = float(a["bench_avg_us"]), float(a["rocprof_avg_us"])
-    assert abs(bench_us / prof_us - 1.0) <= 0.03, (bench_us, prof_us)
+    assert abs(bench_us - prof_us) <= max(0.03 * prof_us, 0.6), (bench_us, prof_us)
     assert abs(float(a["ratio"]) - bench_us / prof_us) < 1e-3
     # the fractions are algorithmic bytes / duration / 8 TB/s, from either duration
     nbytes = float(a["bytes_per_launch"])
