@@ -71,7 +71,9 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
  * follow one another down k, then the next column block, then the next model.
  * netfuse_linear_packed_supported: 1 if netfuse_linear_packed has a kernel for (M, N, K, Nout)
  *   (N a multiple of 128 and Nout a multiple of 96 with K % 256 == 0, or of 128, 288 or 384 with
- *   K % 128 == 0; or N and Nout multiples of 256 with K % 32 == 0) AND the problem is large enough for it to pay (at
+ *   K % 128 == 0; N a multiple of 64 and Nout of 96, 288 or 384 where M * (N / 64) * (Nout / width) lies in
+ *   129 ... 256 -- 64-row tiles, one workgroup per compute unit when 128-row tiles would leave half of them
+ *   idle; or N and Nout multiples of 256 with K % 32 == 0) AND the problem is large enough for it to pay (at
  *   least 128 of its tiles: with few models netfuse_linear's smaller tiles are faster), else 0 (then use
  *   netfuse_linear; netfuse_linear_packed still runs any shape it has a kernel for).
  * netfuse_linear_pack_weight: W[M][K][Nout] -> Wp; W and Wp must not overlap; Wp 16-byte aligned.

@@ -15,9 +15,10 @@
 // another down k.  A wavefront that owns column block j then streams one contiguous run of memory with
 // plain 16-byte register loads (non-temporal: the weights are read once per forward pass), NS k-stages ahead.
 //
-// Workgroup = one (problem, 128-row tile, tile of NB column blocks), NB x KG wavefronts: wavefront (q, j) owns
+// Workgroup = one (problem, tile of RB 32-row blocks -- 128 rows, or 64 where 128-row tiles would leave
+// compute units idle --, tile of NB column blocks), NB x KG wavefronts: wavefront (q, j) owns
 // column block j and, of every k-stage of 16 KG U columns of k, the U 16-k slices q U ... q U + U - 1; it
-// multiplies them with all four 32-row blocks of the A stage (four 16-byte LDS reads per slice, shared by
+// multiplies them with all RB 32-row blocks of the A stage (RB 16-byte LDS reads per slice, shared by
 // nobody: every weight fragment is used by exactly one wavefront, so nothing about B is ever shared).  With
 // KG > 1 (narrow tiles: Nout = 768 gives one tile per compute unit only at 96 columns) the KG partial sums of a
 // 32 x 32 block are added through LDS after the loop, in ascending k-group order, each wavefront finishing one
@@ -32,10 +33,11 @@
 
 namespace nf {
 
-template <int NB, int KG, int U, int NS>
+template <int NB, int KG, int U, int NS, int RB = 4>
 struct FragCfg {
-  static constexpr int kNB = NB, kKG = KG, kU = U, kNS = NS;
-  static constexpr int kBM = 128, kBN = 32 * NB, kBK = 16 * KG * U;
+  static constexpr int kNB = NB, kKG = KG, kU = U, kNS = NS, kRB = RB;      // RB: 32-row blocks per tile
+  static constexpr int kBM = 32 * RB, kBN = 32 * NB, kBK = 16 * KG * U;
+  static_assert(KG == 1 || KG == RB, "with a split k every k-group finishes one 32-row block");
   static_assert(kBK == 32 || kBK == 64, "A stage rows of 64 or 128 bytes");
   static constexpr int kNW = NB * KG, kThreads = kNW * kWave;
   static constexpr int kARow = kBK * 2, kStageBytes = kBM * kARow;       // A stage: [128][BK] bf16, chunks permuted
@@ -64,9 +66,9 @@ __device__ __forceinline__ void static_for(F&& f) {
 // tile (element pointer); C, R, col_bias at the tile's first column.  K a multiple of NS stages.
 template <class Cfg, int NA>
 __device__ __forceinline__ void gemm_frag_loop(const bf16_t* __restrict__ A, long lda, const bf16_t* __restrict__ bsrc,
-                                               int nstage, lds_u8_t* smem, f32x16_t (&acc)[4], int wave, int lane,
+                                               int nstage, lds_u8_t* smem, f32x16_t (&acc)[Cfg::kRB], int wave, int lane,
                                                int q, int a_touch_part, int a_touch_parts, int K) {
-  constexpr int NS = Cfg::kNS, U = Cfg::kU, BK = Cfg::kBK, NW = Cfg::kNW;
+  constexpr int NS = Cfg::kNS, U = Cfg::kU, BK = Cfg::kBK, NW = Cfg::kNW, RB = Cfg::kRB;
   const int half = lane / 32, l32 = lane % 32;
 
   const bf16_t* asrc[NA > 0 ? NA : 1];
@@ -93,9 +95,9 @@ __device__ __forceinline__ void gemm_frag_loop(const bf16_t* __restrict__ A, lon
       asm volatile("global_load_dwordx4 %0, %1, off nt" : "=&v"(bq[slot][u]) : "v"(bsrc + u * 512) : "memory");
     bsrc += (long)Cfg::kKG * U * 512;                       // the next stage's slices of this k-group
   };
-  int a_off[4];
+  int a_off[RB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) a_off[i] = (i * 32 + l32) * Cfg::kARow;
+  for (int i = 0; i < RB; ++i) a_off[i] = (i * 32 + l32) * Cfg::kARow;
   const int a_swz = Cfg::swz_a(l32);
 
   // consume the stage in ring slot r; LEFT = stages issued after it that may still be in flight
@@ -104,18 +106,18 @@ __device__ __forceinline__ void gemm_frag_loop(const bf16_t* __restrict__ A, lon
     wait_vmcnt<LEFT * (NA + U)>();
     __builtin_amdgcn_s_barrier();
     const lds_u8_t* stage = smem + r * Cfg::kStageBytes;
-    bf16x8_t af[U][4];
+    bf16x8_t af[U][RB];
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < RB; ++i)
         af[u][i] = *(const lds_bf16x8_t*)(stage + a_off[i] + (((2 * (q * U + u) + half) ^ a_swz) * 16));
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const bf16x8_t bf = __builtin_bit_cast(bf16x8_t, bq[r][u]);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, af[u][i], acc[i], 0, 0, 0);
+      for (int i = 0; i < RB; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf, af[u][i], acc[i], 0, 0, 0);
     }
     __builtin_amdgcn_sched_barrier(0);
   };
@@ -164,14 +166,14 @@ template <class Cfg>
 __device__ __forceinline__ void gemm_frag_tile(const bf16_t* __restrict__ A, long lda, const bf16_t* __restrict__ Bw,
                                                int K, lds_u8_t* smem, bf16_t* C, const bf16_t* R, long ldc,
                                                const float* col_bias, int act, int a_touch_part, int a_touch_parts) {
-  constexpr int NB = Cfg::kNB, KG = Cfg::kKG, U = Cfg::kU;
+  constexpr int NB = Cfg::kNB, KG = Cfg::kKG, U = Cfg::kU, RB = Cfg::kRB;
   const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int q = wave / NB, j = wave % NB;
 
-  f32x16_t acc[4];
+  f32x16_t acc[RB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < RB; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
@@ -184,18 +186,17 @@ __device__ __forceinline__ void gemm_frag_tile(const bf16_t* __restrict__ A, lon
     gemm_frag_loop<Cfg, Cfg::kNAHi - 1>(A, lda, bsrc, nstage, smem, acc, wave, lane, q, a_touch_part, a_touch_parts, K);
 
   if constexpr (KG == 1) {
-    f32x16_t (&acc2)[4][1] = reinterpret_cast<f32x16_t (&)[4][1]>(acc);
-    if (act == NF_ACT_GELU) reg_epilogue<4, 1, NF_ACT_GELU>(acc2, C, R, ldc, col_bias, 0, 32 * j);
-    else if (act == NF_ACT_RELU) reg_epilogue<4, 1, NF_ACT_RELU>(acc2, C, R, ldc, col_bias, 0, 32 * j);
-    else reg_epilogue<4, 1, NF_ACT_NONE>(acc2, C, R, ldc, col_bias, 0, 32 * j);
+    f32x16_t (&acc2)[RB][1] = reinterpret_cast<f32x16_t (&)[RB][1]>(acc);
+    if (act == NF_ACT_GELU) reg_epilogue<RB, 1, NF_ACT_GELU>(acc2, C, R, ldc, col_bias, 0, 32 * j);
+    else if (act == NF_ACT_RELU) reg_epilogue<RB, 1, NF_ACT_RELU>(acc2, C, R, ldc, col_bias, 0, 32 * j);
+    else reg_epilogue<RB, 1, NF_ACT_NONE>(acc2, C, R, ldc, col_bias, 0, 32 * j);
   } else {
-    static_assert(KG == 1 || KG == 4, "one k-group per 32-row block");
     // Partial sums of row block i go to wavefront (i, j): region of wave d = i NB + j, then [slot][r4][lane] x 16 B,
     // slot = the sender's k-group with the receiver's own left out.
     __builtin_amdgcn_s_barrier();                           // every wave is done reading the A stages
     lds_f32_t* red = (lds_f32_t*)smem;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < RB; ++i) {
       if (i == q) continue;
       const int slot = q < i ? q : q - 1;
       lds_f32_t* dst = red + ((size_t)(i * NB + j) * (KG - 1) + slot) * 1024;
@@ -207,7 +208,7 @@ __device__ __forceinline__ void gemm_frag_tile(const bf16_t* __restrict__ A, lon
     __syncthreads();
     f32x16_t own, sum[1][1];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < RB; ++i)
       if (i == q) own = acc[i];
     const lds_f32_t* src = red + (size_t)wave * (KG - 1) * 1024;
 #pragma unroll

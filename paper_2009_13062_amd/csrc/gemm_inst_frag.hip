@@ -68,6 +68,9 @@ nf_status launch_gemm_frag(int cfg, GemmLaunch& L, hipStream_t s) {
     case F384: return launch_frag<FragCfg<12, 1, 2, NF_FRAG_NS>>(L, s);
     case F128: return launch_frag<FragCfg<4, 1, 2, NF_FRAG_NS>>(L, s);
     case F256: return launch_frag<FragCfg<8, 1, 2, NF_FRAG_NS>>(L, s);
+    case F96h: return launch_frag<FragCfg<3, 2, 2, NF_FRAG_NS, 2>>(L, s);
+    case F288h: return launch_frag<FragCfg<9, 1, 2, NF_FRAG_NS, 2>>(L, s);
+    case F384h: return launch_frag<FragCfg<12, 1, 2, NF_FRAG_NS, 2>>(L, s);
   }
   return NF_EUNSUPPORTED;
 }

@@ -53,12 +53,14 @@ nf_status launch_gemm_stream_packed(int nsub, GemmLaunch& L, hipStream_t s);
 // Fragment-packed weights (gemm_frag.h): B is the output of launch_pack_fragments, sB0/sB1 its problem strides
 // (K x cols elements per problem); 128-row tiles of 96 / 288 / 384 columns (the encoder's widths: one tile per
 // compute unit at 32 models) and of 128 / 256 columns (4 and 8 wavefronts; for widths the first three do not
-// divide).  NF_EUNSUPPORTED if the problem is not whole tiles, K not a whole number of pipeline rounds, or an
+// divide), and the 64-row forms of the first three.  NF_EUNSUPPORTED if the problem is not whole tiles, K not a whole number of pipeline rounds, or an
 // operand not 16-byte aligned.
-enum FragTileId { F96 = 0, F288, F384, F128, F256, kNumFragTiles };
+enum FragTileId { F96 = 0, F288, F384, F128, F256, F96h, F288h, F384h, kNumFragTiles };
 constexpr int kNumFragMainTiles = 3;                             // F96, F288, F384 are tried first
-constexpr int kFragBN[kNumFragTiles] = {96, 288, 384, 128, 256};
-constexpr int kFragKUnit[kNumFragTiles] = {256, 128, 128, 128, 128};      // K must be a multiple of this
+constexpr int kNumFragFullTiles = 5;                             // the 128-row tiles; the rest are their 64-row forms
+constexpr int kFragBN[kNumFragTiles] = {96, 288, 384, 128, 256, 96, 288, 384};
+constexpr int kFragBM[kNumFragTiles] = {128, 128, 128, 128, 128, 64, 64, 64};
+constexpr int kFragKUnit[kNumFragTiles] = {256, 128, 128, 128, 128, 256, 128, 128};      // K must be a multiple of this
 nf_status launch_gemm_frag(int cfg, GemmLaunch& L, hipStream_t s);
 // W[problems][K][Nout] -> fragment order (pack_kernels.h); K % 16 == 0, Nout % 32 == 0
 nf_status launch_pack_fragments(const bf16_t* W, bf16_t* Wp, long long problems, int K, int Nout, hipStream_t s);

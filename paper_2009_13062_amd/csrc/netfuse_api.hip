@@ -308,22 +308,42 @@ nf_status netfuse_linear(const void* X, const void* W, const float* bias, const 
 // The fragment-packed kernel for (N, K, Nout) at M models: the tile width that needs the fewest rounds of
 // workgroups over the 256 compute units, weighted by its width (a round streams width x K weights per unit);
 // ties go to the wider tile.  -1 if no tile fits.
+#ifndef NF_FRAG_HALF_TILES
+#define NF_FRAG_HALF_TILES 1
+#endif
 static int pick_frag(int N, int Nout, int K, int M) {
-  if (N % 128 != 0) return -1;
+  static const int forced = [] { const char* e = dev_getenv("NETFUSE_FRAG"); return e ? atoi(e) : -1; }();
+  auto fits = [&](int t) { return N % kFragBM[t] == 0 && Nout % kFragBN[t] == 0 && K % kFragKUnit[t] == 0; };
+  if (forced >= 0 && forced < kNumFragTiles && fits(forced)) return forced;
+  auto tiles_of = [&](int t) { return (long long)M * (N / kFragBM[t]) * (Nout / kFragBN[t]); };
   auto best_of = [&](int lo, int hi) {
     int best = -1;
     long long best_cost = 0;
     for (int t = lo; t < hi; ++t) {
-      if (Nout % kFragBN[t] || K % kFragKUnit[t]) continue;
-      const long long tiles = (long long)M * (N / 128) * (Nout / kFragBN[t]);
-      const long long cost = (tiles + 255) / 256 * kFragBN[t];
+      if (!fits(t)) continue;
+      const long long cost = (tiles_of(t) + 255) / 256 * kFragBN[t];
       if (best < 0 || cost < best_cost || (cost == best_cost && kFragBN[t] > kFragBN[best])) { best = t; best_cost = cost; }
     }
     return best;
   };
   // the 12- and 9-wavefront tiles wherever one of them divides the width, else the 128 / 256 column ones
-  const int main_tile = best_of(0, kNumFragMainTiles);
-  return main_tile >= 0 ? main_tile : best_of(kNumFragMainTiles, kNumFragTiles);
+  int pick = best_of(0, kNumFragMainTiles);
+  if (pick < 0) pick = best_of(kNumFragMainTiles, kNumFragFullTiles);
+  // With fewer models the 128-row tiles leave compute units idle or need a second, half empty round.  The
+  // 64-row form of a width doubles the workgroups; the two row tiles of a column tile run side by side and share
+  // its weights through L2, so a compute unit's weight stream costs about half as much as one of its own
+  // (factor 0.45).  Only where that gives one round of more than 128 workgroups.  Measured at 16 models and 128
+  // rows (us): 3072 -> 768 32.7 -> 24.5, 768 -> 768 12.8 -> 10.0 (96 columns), 768 -> 2304 24.4 -> 18.4 (288 against 96),
+  // 768 -> 3072 29.2 -> 23.2 (384 against 96); forward 1.38 -> 1.15 ms.  At 8 models they lose against what runs now.
+  if (NF_FRAG_HALF_TILES) {
+    long long best_cost = pick < 0 ? -1 : 100 * ((tiles_of(pick) + 255) / 256 * kFragBN[pick]);
+    for (int t = kNumFragFullTiles; t < kNumFragTiles; ++t) {
+      if (!fits(t) || tiles_of(t) <= 128 || tiles_of(t) > 256) continue;
+      const long long cost = 45LL * kFragBN[t];
+      if (best_cost < 0 || cost < best_cost) { pick = t; best_cost = cost; }
+    }
+  }
+  return pick;
 }
 
 // The 256 x 256 streaming kernel on packed weights (several column tiles per workgroup through one pipeline;
@@ -358,7 +378,7 @@ int netfuse_linear_packed_supported(int M, int N, int K, int Nout, nf_dtype dt) 
   // With few models the 128-row tiles leave most compute units idle and netfuse_linear's small tiles win
   // (one encoder layer at 8 models: 0.088 ms packed against 0.074 ms; at 16 models packed is ahead): the answer
   // is "no" below half a workgroup per compute unit, although netfuse_linear_packed itself still runs there.
-  const long long tiles = (long long)M * (N / 128) * (Nout / kFragBN[f]);
+  const long long tiles = (long long)M * (N / kFragBM[f]) * (Nout / kFragBN[f]);
   return tiles >= 128 ? 1 : 0;
 }
 

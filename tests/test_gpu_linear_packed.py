@@ -53,6 +53,13 @@ PACKED_CASES = [
     (16, 128, 1024, 1024, True, True, 0),
     (8, 128, 1024, 4096, True, False, 2),
     (3, 128, 256, 640, False, True, 1),       # five tiles of 128
+    # 64-row tiles (fewer models: one round of 129 ... 256 workgroups instead of half a round of 128-row tiles)
+    (16, 128, 768, 2304, True, False, 0),     # 64 x 288
+    (16, 128, 768, 3072, True, False, 2),     # 64 x 384, GELU
+    (16, 128, 3072, 768, True, True, 0),      # 64 x 96, two k-groups reduced through LDS, residual
+    (16, 128, 768, 768, True, True, 1),       # 64 x 96, ReLU before the residual
+    (8, 256, 768, 768, False, True, 0),       # four 64-row tiles per model
+    (43, 192, 256, 96, True, False, 0),       # three 64-row tiles per model: rows no 128-row tile divides
 ]
 
 
